@@ -1,0 +1,195 @@
+/*
+ * cornenc -- the encoder task and the embedding hand-off of a disaggregated
+ * multimodal serving system, as a C-ABI library for one MI355X (gfx950).
+ *
+ * The paper splits a multimodal LLM at the encoder boundary (Sec. 3.1 "Model
+ * Fission", Listing 1): an encoder task, run by its own executor on its own GPU
+ * (Sec. 2 "Data Plane"), turns every multimodal item of a request into one
+ * embedding tensor; the tensors are appended to the request in item order; the
+ * LLM task, created to receive embeddings, does not run an encoder and takes the
+ * tensors forwarded to it (Sec. 3.1 "Data Forwarding").  This library is the GPU
+ * compute on both sides of that boundary:
+ *
+ *   cs_encode              the encoder task on one packed, variable-length batch
+ *   cs_forward_embeddings  the consumer-side placement of received embedding rows
+ *                          into the LLM's input-embedding buffer
+ *
+ * The paper does not describe the inside of an encoder.  Two towers are built:
+ * a Qwen2.5-VL-style vision transformer (RMSNorm, 2-D/3-D rotary, window and
+ * full attention, SwiGLU, 2x2 patch merger) and a Whisper-style audio encoder
+ * (two k=3 convolutions, sinusoidal positions, LayerNorm, GELU MLP, pair pooling
+ * and projection).
+ *
+ * General rules
+ *  - No call throws or aborts.  Every call returns a cs_status; cs_last_error()
+ *    gives a thread-local text for the last failure on the calling thread.
+ *  - "dev" pointers are device memory of the current HIP device, "host" pointers
+ *    are ordinary host memory.  All dev pointers must be 16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The two
+ *    hot calls only enqueue work on it and return; arguments are validated on the
+ *    host before anything is enqueued.
+ *  - The caller owns every buffer it passes in, the workspace included.  The library
+ *    owns its repacked copy of the weights and small host staging buffers.
+ */
+#ifndef CORNENC_H
+#define CORNENC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CS_OK = 0,
+  CS_ERR_INVALID_ARG = 1, /* NULL pointer, misaligned pointer, bad enum, bad size   */
+  CS_ERR_SHAPE = 2,       /* cu_seqlens / grid_thw inconsistent, odd grid, ...      */
+  CS_ERR_WORKSPACE = 3,   /* workspace smaller than cs_encoder_query reports        */
+  CS_ERR_INDEX = 4,       /* reserved for host-side index checks                    */
+  CS_ERR_UNSUPPORTED = 5, /* a configuration the kernels are not built for          */
+  CS_ERR_HIP = 6,         /* a HIP runtime call failed (text in cs_last_error)      */
+  CS_ERR_MISSING_WEIGHT = 7
+} cs_status;
+
+typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
+typedef enum { CS_ARCH_VIT = 0, CS_ARCH_AUDIO = 1 } cs_arch;
+
+/* Encoder description.  Plain data; set struct_size = sizeof(cs_encoder_config). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t arch;          /* cs_arch */
+  int32_t dtype;         /* cs_dtype of the weights passed to create and of `patches` */
+  int32_t out_dtype;     /* cs_dtype of the embedding rows cs_encode writes          */
+  int32_t patch_dim;     /* vit: 3*tp*14*14 (1176); audio: mel bins (128)            */
+  int32_t hidden;        /* 1280                                                     */
+  int32_t n_heads;       /* 16 (audio 20)                                            */
+  int32_t head_dim;      /* 80 (audio 64); n_heads*head_dim == hidden                */
+  int32_t n_layers;      /* 32, at most 64                                           */
+  int32_t mlp_dim;       /* 3420 (audio 5120)                                        */
+  int32_t merge;         /* vit: side of the merged patch square (2); audio: frames pooled (2) */
+  int32_t merger_hidden; /* vit: width between the two merger linears (5120)         */
+  int32_t out_hidden;    /* 3584                                                     */
+  int32_t window;        /* vit: window side in patches (8); <= 0: every layer full  */
+  uint64_t full_attn_layer_mask; /* bit l set: layer l attends over the whole item   */
+  int32_t rope_sections[3];      /* rotary pairs for (t,row,col); sum == head_dim/2; audio: all 0 */
+  float rope_theta;      /* 10000                                                    */
+  float norm_eps;        /* 1e-6 (audio 1e-5)                                        */
+  int32_t conv_kernel;   /* audio: 3                                                 */
+} cs_encoder_config;
+
+/* One named weight, HOST memory, element type = config.dtype (bf16 as raw 16-bit words),
+ * row-major, Linear weights as [out_features, in_features].  Names:
+ *  vit:   patch_embed.weight [hidden,patch_dim]
+ *         blocks.{l}.norm1.weight [hidden]          blocks.{l}.norm2.weight [hidden]
+ *         blocks.{l}.attn.qkv.weight [3*hidden,hidden]  (rows: q | k | v, each head-major)  .bias
+ *         blocks.{l}.attn.proj.weight [hidden,hidden]   .bias
+ *         blocks.{l}.mlp.gate.weight / mlp.up.weight [mlp_dim,hidden]  .bias
+ *         blocks.{l}.mlp.down.weight [hidden,mlp_dim]   .bias
+ *         merger.norm.weight [hidden]
+ *         merger.fc1.weight [merger_hidden, merge*merge*hidden] .bias
+ *         merger.fc2.weight [out_hidden, merger_hidden]         .bias
+ *  audio: conv1.weight [hidden,patch_dim,3] .bias   conv2.weight [hidden,hidden,3] .bias
+ *         blocks.{l}.norm1.weight/.bias  norm2.weight/.bias
+ *         blocks.{l}.attn.qkv.weight/.bias  attn.proj.weight/.bias
+ *         blocks.{l}.mlp.fc1.weight [mlp_dim,hidden] .bias  mlp.fc2.weight [hidden,mlp_dim] .bias
+ *         post.norm.weight/.bias   post.proj.weight [out_hidden,hidden] .bias
+ * A bias that is absent from the list is taken as zero; any other absent tensor is an error. */
+typedef struct {
+  const char* name;
+  const void* data; /* host */
+  int64_t numel;
+} cs_tensor;
+
+typedef struct cs_encoder cs_encoder;
+
+/* Builds an encoder: checks the configuration, converts and repacks the weights on the
+ * host (padding, row interleaving for fused epilogues), and copies them to the current
+ * device.  The caller may free `weights` afterwards.  Blocks until the copy is done. */
+cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* weights, int32_t n_weights,
+                            cs_encoder** out_encoder);
+
+/* Frees device and host memory of the encoder.  The caller must have synchronised every
+ * stream that still runs work of this encoder.  NULL is ignored. */
+void cs_encoder_destroy(cs_encoder* enc);
+
+/* Host-only: validates a batch description and reports how many embedding rows cs_encode
+ * will write and how large a workspace it needs.  cu_seqlens, grid_thw as for cs_encode. */
+cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                           int32_t n_items, int64_t* n_out_rows, size_t* workspace_bytes);
+
+/* The encoder task (Sec. 2 "Data Plane": the executor for image, video and audio encoders;
+ * Listing 1: one embedding tensor per multimodal item, in item order).
+ *
+ *  patches         dev  [N, patch_dim], config.dtype.  vit: the patches of all items packed
+ *                       back to back, inside an item in raster order (t, row, col), inside a
+ *                       patch in the order (channel, temporal, py, px).  audio: log-mel frames,
+ *                       frame-major (row = frame, column = mel bin).
+ *  cu_seqlens      host [n_items+1], cu_seqlens[0] = 0, item i owns rows [cu[i], cu[i+1]).
+ *  grid_thw        host [n_items,3] = (t, h, w) in patches, h and w multiples of `merge`,
+ *                       t*h*w == cu[i+1]-cu[i].  audio: (1, 1, frames), frames a multiple of 4.
+ *  out_embeddings  dev  [M, out_hidden], config.out_dtype.  vit: item i yields t*(h/2)*(w/2) rows
+ *                       in raster order of the merged grid; audio: frames/4 rows; items in input
+ *                       order.  M = sum over items (cs_encoder_query reports it).
+ *  workspace       dev, at least the size cs_encoder_query reports for this batch; contents
+ *                       are scratch.  Two calls that overlap in time need two workspaces.
+ *
+ * Errors are reported before any work is enqueued: CS_ERR_INVALID_ARG, CS_ERR_SHAPE,
+ * CS_ERR_WORKSPACE.  Results are deterministic: the same inputs give the same bits. */
+cs_status cs_encode(cs_encoder* enc, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                    int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* The hand-off on the consumer side (Sec. 3.1 "Data Forwarding": the receiver copies the
+ * forwarded tensor into its GPU memory; Listing 1: the LLM task takes embeddings instead of
+ * encoding):  dst_seq[placeholder_index[i], :] = src[i, :]  as a copy of storage words.
+ *
+ *  src                dev [n_rows, hidden] rows of `dtype`
+ *  placeholder_index  dev [n_rows] int64, flat row number in dst_seq; -1 skips the row
+ *  dst_seq            dev [dst_rows, hidden]; rows not named by an index are not touched
+ *  err_flag           dev int32 or NULL; set to 1 if any index is < -1 or >= dst_rows
+ *                     (that row is skipped, nothing is written out of bounds); never cleared
+ *                     by the library
+ * hidden * sizeof(dtype) must be a multiple of 16.  Two source rows with the same index are a
+ * caller error (one of them wins).  n_rows == 0 is a no-op. */
+cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_index, void* dst_seq,
+                                int64_t n_rows, int64_t dst_rows, int32_t hidden, int32_t dtype,
+                                int32_t* err_flag, void* stream);
+
+/* Host-only (no GPU needed) view of the token plan cs_encode builds for a vit batch with this
+ * configuration; also validates the batch description exactly as cs_encode does.
+ * The towers work in an internal token order: item, frame, window (row-major over the
+ * window grid), 2x2 merge group (row-major inside the window), patch inside the group.
+ *  src_row   [N]   raster patch row feeding internal token i
+ *  out_row   [N/4] output embedding row written by internal merged token j
+ *  win_cu    [n_windows+1] internal-token boundaries of the attention windows
+ * Any output pointer may be NULL.  *n_windows receives the number of windows. */
+cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                         int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
+                         int32_t win_cu_capacity, int32_t* n_windows);
+
+/* Component calls: the two contraction kernels on their own, for parity tests and
+ * micro-benchmarks.  All pointers dev.
+ *
+ * cs_linear_bf16:  C[m,n] = sum_k A[m,k] * W[n,k] + bias[n]   (bias may be NULL)
+ *  A bf16 [M,lda] (lda >= K), W bf16 [N,K] with K a multiple of 64, C [M,N] of c_dtype. */
+cs_status cs_linear_bf16(const void* A, int64_t lda, const void* W, const float* bias, void* C,
+                         int32_t c_dtype, int64_t M, int32_t N, int32_t K, void* stream);
+
+/* cs_attention_varlen: softmax(q k^T) v per head inside each segment; q already carries the
+ * softmax scale times log2(e) (scores are exponentiated with exp2).
+ *  qk   bf16 [N_tok, 2*n_heads*head_dim]  (q | k, head-major)
+ *  vt   bf16 [n_heads*head_dim, ld_vt]    v transposed: vt[h*head_dim+d, token]
+ *  seg_cu host int32 [n_seg+1] token boundaries, multiples of 4
+ *  out  bf16 [N_tok, n_heads*head_dim]
+ * head_dim 64 or 80. */
+cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
+                              int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream);
+
+const char* cs_status_string(cs_status s);
+const char* cs_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CORNENC_H */

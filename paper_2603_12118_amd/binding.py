@@ -1,0 +1,215 @@
+"""ctypes binding of libcornenc.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/cornenc.h).  PyTorch
+tensors are used as device memory and for the current HIP stream; no step of the encoder runs
+in Python.  Importing this module needs the built library; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcornenc.so")
+
+CS_F32, CS_BF16 = 0, 1
+CS_ARCH_VIT, CS_ARCH_AUDIO = 0, 1
+
+
+class CsError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"cornenc status {status}: {text}")
+        self.status = status
+
+
+class cs_encoder_config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("arch", C.c_int32), ("dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("patch_dim", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("n_layers", C.c_int32), ("mlp_dim", C.c_int32), ("merge", C.c_int32), ("merger_hidden", C.c_int32),
+                ("out_hidden", C.c_int32), ("window", C.c_int32), ("full_attn_layer_mask", C.c_uint64),
+                ("rope_sections", C.c_int32 * 3), ("rope_theta", C.c_float), ("norm_eps", C.c_float),
+                ("conv_kernel", C.c_int32)]
+
+
+class cs_tensor(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("data", C.c_void_p), ("numel", C.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                               "(python -m paper_2603_12118_amd.build)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32p, i64 = C.c_void_p, C.POINTER(C.c_int32), C.c_int64
+        L.cs_encoder_create.argtypes = [C.POINTER(cs_encoder_config), C.POINTER(cs_tensor), C.c_int32, C.POINTER(vp)]
+        L.cs_encoder_destroy.argtypes = [vp]
+        L.cs_encoder_destroy.restype = None
+        L.cs_encoder_query.argtypes = [vp, i32p, i32p, C.c_int32, C.POINTER(i64), C.POINTER(C.c_size_t)]
+        L.cs_encode.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.cs_forward_embeddings.argtypes = [vp, vp, vp, i64, i64, C.c_int32, C.c_int32, vp, vp]
+        L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
+        L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
+        L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.cs_status_string.argtypes = [C.c_int]
+        L.cs_status_string.restype = C.c_char_p
+        L.cs_last_error.restype = C.c_char_p
+        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
+                  "cs_linear_bf16", "cs_attention_varlen"):
+            getattr(L, f).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        L = lib()
+        raise CsError(status, f"{L.cs_status_string(status).decode()}: {L.cs_last_error().decode()}")
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _i32p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _stream(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def make_config(cfg) -> cs_encoder_config:
+    """workloads.EncoderConfig -> C struct."""
+    c = cs_encoder_config()
+    c.struct_size = C.sizeof(cs_encoder_config)
+    c.arch = CS_ARCH_VIT if cfg.arch == "vit" else CS_ARCH_AUDIO
+    c.dtype = CS_BF16 if cfg.dtype == "bf16" else CS_F32
+    c.out_dtype = CS_BF16 if cfg.out_dtype == "bf16" else CS_F32
+    for k in ("patch_dim", "hidden", "n_heads", "head_dim", "n_layers", "mlp_dim", "merge", "merger_hidden",
+              "out_hidden", "window", "conv_kernel"):
+        setattr(c, k, int(getattr(cfg, k)))
+    mask = 0
+    for l in cfg.full_attn_layers:
+        mask |= 1 << int(l)
+    c.full_attn_layer_mask = mask
+    c.rope_sections = (C.c_int32 * 3)(*[int(s) for s in cfg.rope_sections])
+    c.rope_theta = float(cfg.rope_theta)
+    c.norm_eps = float(cfg.norm_eps)
+    return c
+
+
+class Encoder:
+    """Owns a cs_encoder handle."""
+
+    def __init__(self, cfg, weights: Dict[str, np.ndarray]):
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        cc = make_config(cfg)
+        keep, arr = [], (cs_tensor * len(weights))()
+        for i, (name, w) in enumerate(weights.items()):
+            w32 = np.ascontiguousarray(w, dtype=np.float32)
+            if cfg.dtype == "bf16":      # values are bf16-representable: hand over the 16-bit words
+                buf = np.ascontiguousarray((w32.view(np.uint32) >> np.uint32(16)).astype(np.uint16))
+            else:
+                buf = w32
+            keep.append(buf)
+            arr[i].name = name.encode()
+            arr[i].data = buf.ctypes.data
+            arr[i].numel = buf.size
+        _check(lib().cs_encoder_create(C.byref(cc), arr, len(weights), C.byref(self._h)))
+
+    def close(self) -> None:
+        if self._h:
+            lib().cs_encoder_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def cs_encoder_query(self, cu_seqlens, grid_thw):
+        cu, g = _i32(cu_seqlens), _i32(grid_thw)
+        n_out, ws = C.c_int64(), C.c_size_t()
+        _check(lib().cs_encoder_query(self._h, _i32p(cu), _i32p(g), g.shape[0], C.byref(n_out), C.byref(ws)))
+        return n_out.value, ws.value
+
+    def cs_encode(self, patches, cu_seqlens, grid_thw, out=None, workspace=None, stream=None):
+        """patches: device tensor [N, patch_dim] of the config dtype.  Returns (out, workspace)."""
+        import torch
+        cu, g = _i32(cu_seqlens), _i32(grid_thw)
+        n_out, ws_bytes = self.cs_encoder_query(cu, g)
+        if out is None:
+            dt = torch.bfloat16 if self.cfg.out_dtype == "bf16" else torch.float32
+            out = torch.empty((n_out, self.cfg.out_hidden), dtype=dt, device=patches.device)
+        if workspace is None or workspace.numel() < ws_bytes:
+            workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=patches.device)
+        assert patches.is_contiguous() and out.is_contiguous()
+        _check(lib().cs_encode(self._h, patches.data_ptr(), _i32p(cu), _i32p(g), g.shape[0], out.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(), _stream(stream)))
+        return out, workspace
+
+
+def cs_plan_tokens(cfg, cu_seqlens, grid_thw):
+    """Host-only: (src_row, out_row, win_cu) of the internal token order for a vit batch."""
+    cu, g = _i32(cu_seqlens), _i32(grid_thw)
+    cc = make_config(cfg)
+    n = max(int(cu[-1]), 0) if len(cu) else 0
+    src_row, out_row = np.empty(max(n, 1), np.int32), np.empty(max(n // 4, 1), np.int32)
+    win_cu, nw = np.empty(n + 2, np.int32), C.c_int32()
+    _check(lib().cs_plan_tokens(C.byref(cc), _i32p(cu), _i32p(g), g.shape[0] if g.ndim == 2 else 0, _i32p(src_row),
+                                _i32p(out_row), _i32p(win_cu), n + 2, C.byref(nw)))
+    return src_row[:n], out_row[:n // 4], win_cu[:nw.value + 1].copy()
+
+
+def cs_forward_embeddings(src, placeholder_index, dst_seq, err_flag=None, stream=None) -> None:
+    """dst_seq[placeholder_index[i], :] = src[i, :] on the GPU (device tensors)."""
+    import torch
+    assert src.is_contiguous() and dst_seq.is_contiguous() and placeholder_index.dtype == torch.int64
+    assert src.dtype == dst_seq.dtype and src.dim() == 2 and dst_seq.dim() == 2
+    if src.dtype == torch.bfloat16:
+        dt = CS_BF16
+    elif src.dtype == torch.float32:
+        dt = CS_F32
+    else:
+        raise TypeError("rows must be bf16 or fp32")
+    _check(lib().cs_forward_embeddings(src.data_ptr(), placeholder_index.data_ptr(), dst_seq.data_ptr(),
+                                       src.shape[0], dst_seq.shape[0], src.shape[1], dt,
+                                       err_flag.data_ptr() if err_flag is not None else None, _stream(stream)))
+
+
+def cs_forward_embeddings_raw(src_ptr, idx_ptr, dst_ptr, n_rows, dst_rows, hidden, dtype, err_ptr=None, stream=0) -> int:
+    """The C call with plain integers, returning the status (for argument-validation tests)."""
+    return lib().cs_forward_embeddings(src_ptr, idx_ptr, dst_ptr, n_rows, dst_rows, hidden, dtype, err_ptr, stream)
+
+
+def cs_linear_bf16(A, W, bias, out, stream=None) -> None:
+    import torch
+    M, K = A.shape
+    N = W.shape[0]
+    assert A.dtype == torch.bfloat16 and W.dtype == torch.bfloat16 and W.shape[1] == K
+    assert out.shape == (M, N) and out.is_contiguous() and W.is_contiguous() and A.stride(1) == 1
+    _check(lib().cs_linear_bf16(A.data_ptr(), A.stride(0), W.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                out.data_ptr(), CS_BF16 if out.dtype == torch.bfloat16 else CS_F32, M, N, K,
+                                _stream(stream)))
+
+
+def cs_attention_varlen(qk, vt, out, seg_cu: Sequence[int], n_heads: int, head_dim: int, stream=None) -> None:
+    seg = _i32(seg_cu)
+    _check(lib().cs_attention_varlen(qk.data_ptr(), vt.data_ptr(), vt.stride(0), out.data_ptr(), _i32p(seg),
+                                     len(seg) - 1, n_heads, head_dim, _stream(stream)))
+
+
+def last_error() -> str:
+    return lib().cs_last_error().decode()

@@ -1,0 +1,639 @@
+// C ABI of the library: error text, encoder creation (weight conversion and repacking on the
+// host), batch query, the encoder task itself (a fixed sequence of kernel launches on the
+// caller's stream) and the embedding hand-off.
+#include <math.h>
+#include <string.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "plan.h"
+
+namespace cs {
+
+static thread_local std::string g_last_error;
+void set_error(const std::string& msg) { g_last_error = msg; }
+cs_status fail(cs_status s, const std::string& msg) {
+  g_last_error = msg;
+  return s;
+}
+
+static inline bf16_t host_f2bf(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+static inline float host_bf2f(bf16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+// A weight as the caller passed it, readable element by element as float.
+struct SrcTensor {
+  const void* data = nullptr;
+  int64_t numel = 0;
+  int dtype = CS_F32;
+  float at(int64_t i) const {
+    return dtype == CS_BF16 ? host_bf2f(static_cast<const bf16_t*>(data)[i]) : static_cast<const float*>(data)[i];
+  }
+  bf16_t bits(int64_t i) const {
+    return dtype == CS_BF16 ? static_cast<const bf16_t*>(data)[i] : host_f2bf(static_cast<const float*>(data)[i]);
+  }
+};
+
+// Host image of the device weight arena.
+struct Arena {
+  std::vector<unsigned char> host;
+  size_t alloc(size_t bytes) {
+    const size_t off = (size_t)round_up((int64_t)host.size(), 256);
+    host.resize(off + bytes, 0);
+    return off;
+  }
+  bf16_t* bf(size_t off) { return reinterpret_cast<bf16_t*>(host.data() + off); }
+  float* f32(size_t off) { return reinterpret_cast<float*>(host.data() + off); }
+};
+
+struct LayerW {
+  size_t wqkv, bqkv, wo, bo, w1, b1, w2, b2;  // w1: gate|up interleaved (vit) or fc1 (audio); w2: down / fc2
+  size_t g1, be1, g2, be2;                    // norm gains and (audio) norm biases
+};
+
+}  // namespace cs
+
+using namespace cs;
+
+struct cs_encoder {
+  cs_encoder_config cfg;
+  int device = 0;
+  // derived sizes
+  int P_pad = 0, I_pad = 0, MH_pad = 0, half = 0;
+  bool rope = false;
+  // weights
+  unsigned char* dev = nullptr;
+  size_t dev_bytes = 0;
+  std::vector<LayerW> layers;
+  size_t w_pe = 0, g_m = 0, w_m1 = 0, b_m1 = 0, w_m2 = 0, b_m2 = 0;          // vit
+  size_t w_c1 = 0, b_c1 = 0, w_c2 = 0, b_c2 = 0, g_p = 0, be_p = 0, w_p = 0, b_p = 0, pe_tab = 0;  // audio
+  size_t inv_freq = 0, axis = 0;
+  int pe_positions = 0;
+  // pinned staging for the per-batch index tables, two slots used in turn
+  void* stage[2] = {nullptr, nullptr};
+  size_t stage_cap[2] = {0, 0};
+  hipEvent_t stage_ev[2] = {nullptr, nullptr};
+  bool stage_used[2] = {false, false};
+  int stage_next = 0;
+
+  template <class T>
+  T* ptr(size_t off) const { return reinterpret_cast<T*>(dev + off); }
+};
+
+namespace cs {
+
+static cs_status check_config(const cs_encoder_config& c) {
+  if (c.struct_size != sizeof(cs_encoder_config)) return fail(CS_ERR_INVALID_ARG, "config.struct_size mismatch");
+  if (c.arch != CS_ARCH_VIT && c.arch != CS_ARCH_AUDIO) return fail(CS_ERR_INVALID_ARG, "config.arch");
+  if ((c.dtype != CS_F32 && c.dtype != CS_BF16) || (c.out_dtype != CS_F32 && c.out_dtype != CS_BF16))
+    return fail(CS_ERR_INVALID_ARG, "config.dtype / out_dtype");
+  if (c.hidden <= 0 || c.n_heads <= 0 || c.head_dim <= 0 || c.n_heads * c.head_dim != c.hidden)
+    return fail(CS_ERR_INVALID_ARG, "config: n_heads * head_dim must equal hidden");
+  if (c.head_dim != 64 && c.head_dim != 80) return fail(CS_ERR_UNSUPPORTED, "config: head_dim must be 64 or 80");
+  if (c.hidden % 64 || c.hidden > 2048) return fail(CS_ERR_UNSUPPORTED, "config: hidden must be a multiple of 64, at most 2048");
+  if (c.n_layers <= 0 || c.n_layers > 64) return fail(CS_ERR_UNSUPPORTED, "config: 1..64 layers");
+  if (c.mlp_dim <= 0 || c.out_hidden <= 0 || c.patch_dim <= 0) return fail(CS_ERR_INVALID_ARG, "config: sizes");
+  if (c.patch_dim % 4) return fail(CS_ERR_UNSUPPORTED, "config: patch_dim must be a multiple of 4");
+  if ((c.out_hidden * (c.out_dtype == CS_BF16 ? 2 : 4)) % 16)
+    return fail(CS_ERR_UNSUPPORTED, "config: an output row must be a multiple of 16 bytes");
+  if (c.arch == CS_ARCH_VIT) {
+    if (c.merge != 2) return fail(CS_ERR_UNSUPPORTED, "config: merge must be 2");
+    if (c.merger_hidden <= 0) return fail(CS_ERR_INVALID_ARG, "config: merger_hidden");
+    if (c.window > 0 && c.window % c.merge) return fail(CS_ERR_UNSUPPORTED, "config: window must be a multiple of merge");
+    const int s = c.rope_sections[0] + c.rope_sections[1] + c.rope_sections[2];
+    if (c.rope_sections[0] < 0 || c.rope_sections[1] < 0 || c.rope_sections[2] < 0 || (s != 0 && s != c.head_dim / 2))
+      return fail(CS_ERR_INVALID_ARG, "config: rope_sections must sum to head_dim/2 (or all be 0)");
+    if (s && !(c.rope_theta > 0)) return fail(CS_ERR_INVALID_ARG, "config: rope_theta");
+  } else {
+    if (c.merge < 1 || c.merge > 8) return fail(CS_ERR_UNSUPPORTED, "config: pool must be 1..8");
+    if (c.conv_kernel != 3) return fail(CS_ERR_UNSUPPORTED, "config: conv_kernel must be 3");
+    if (c.patch_dim % 64) return fail(CS_ERR_UNSUPPORTED, "config: mel bins must be a multiple of 64");
+  }
+  if (!(c.norm_eps >= 0)) return fail(CS_ERR_INVALID_ARG, "config: norm_eps");
+  return CS_OK;
+}
+
+struct WeightBook {
+  std::map<std::string, SrcTensor> m;
+  int dtype;
+  cs_status get(const std::string& name, int64_t numel, SrcTensor& out, bool optional = false) const {
+    auto it = m.find(name);
+    if (it == m.end()) {
+      if (optional) {
+        out = SrcTensor();
+        return CS_OK;
+      }
+      return fail(CS_ERR_MISSING_WEIGHT, "missing weight: " + name);
+    }
+    if (it->second.numel != numel)
+      return fail(CS_ERR_SHAPE, "weight " + name + ": expected " + std::to_string(numel) + " elements, got " +
+                                    std::to_string(it->second.numel));
+    out = it->second;
+    return CS_OK;
+  }
+};
+
+// [rows, cols] -> bf16 [rows_pad, cols_pad] zero padded, row r taken from source row row_of(r)
+template <class RowOf>
+static size_t pack_matrix(Arena& A, const SrcTensor& t, int64_t rows_pad, int64_t cols, int64_t cols_pad, RowOf row_of) {
+  const size_t off = A.alloc((size_t)rows_pad * cols_pad * 2);
+  for (int64_t r = 0; r < rows_pad; ++r) {
+    const int64_t sr = row_of(r);
+    if (sr < 0) continue;
+    bf16_t* d = A.bf(off) + r * cols_pad;
+    if (t.dtype == CS_BF16) {
+      memcpy(d, static_cast<const bf16_t*>(t.data) + sr * cols, (size_t)cols * 2);
+    } else {
+      const float* s = static_cast<const float*>(t.data) + sr * cols;
+      for (int64_t c = 0; c < cols; ++c) d[c] = host_f2bf(s[c]);
+    }
+  }
+  return off;
+}
+
+template <class RowOf>
+static size_t pack_vector(Arena& A, const SrcTensor& t, int64_t n_pad, RowOf idx_of) {
+  const size_t off = A.alloc((size_t)n_pad * 4);
+  if (!t.data) return off;  // absent bias: zeros
+  for (int64_t i = 0; i < n_pad; ++i) {
+    const int64_t si = idx_of(i);
+    if (si >= 0) A.f32(off)[i] = t.at(si);
+  }
+  return off;
+}
+
+static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
+  const cs_encoder_config& c = e->cfg;
+  const int64_t D = c.hidden, I = c.mlp_dim, dh = c.head_dim;
+  auto ident = [](int64_t r) { return r; };
+  SrcTensor t, b;
+  // q and k rows are permuted inside every head so that the two members of rotary pair j
+  // (dims j and j + dh/2) sit in neighbouring columns 2j, 2j+1; q.k is unchanged by a common permutation.
+  auto qkv_row = [&](int64_t r) -> int64_t {
+    if (!e->rope || r >= 2 * D) return r;
+    const int64_t base = r - r % dh, p = r % dh;
+    return base + ((p & 1) ? p / 2 + dh / 2 : p / 2);
+  };
+  e->layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const std::string p = "blocks." + std::to_string(l) + ".";
+    LayerW& L = e->layers[l];
+    if (cs_status st = wb.get(p + "norm1.weight", D, t)) return st;
+    L.g1 = pack_vector(A, t, D, ident);
+    if (cs_status st = wb.get(p + "norm2.weight", D, t)) return st;
+    L.g2 = pack_vector(A, t, D, ident);
+    L.be1 = L.be2 = 0;
+    if (c.arch == CS_ARCH_AUDIO) {
+      if (cs_status st = wb.get(p + "norm1.bias", D, t, true)) return st;
+      L.be1 = pack_vector(A, t, D, ident);
+      if (cs_status st = wb.get(p + "norm2.bias", D, t, true)) return st;
+      L.be2 = pack_vector(A, t, D, ident);
+    }
+    if (cs_status st = wb.get(p + "attn.qkv.weight", 3 * D * D, t)) return st;
+    if (cs_status st = wb.get(p + "attn.qkv.bias", 3 * D, b, true)) return st;
+    L.wqkv = pack_matrix(A, t, 3 * D, D, D, qkv_row);
+    L.bqkv = pack_vector(A, b, 3 * D, qkv_row);
+    if (cs_status st = wb.get(p + "attn.proj.weight", D * D, t)) return st;
+    if (cs_status st = wb.get(p + "attn.proj.bias", D, b, true)) return st;
+    L.wo = pack_matrix(A, t, D, D, D, ident);
+    L.bo = pack_vector(A, b, D, ident);
+    if (c.arch == CS_ARCH_VIT) {
+      // gate and up rows interleaved in blocks of 32 so that one lane holds gate_j and up_j
+      SrcTensor tg, tu, bg, bu;
+      if (cs_status st = wb.get(p + "mlp.gate.weight", I * D, tg)) return st;
+      if (cs_status st = wb.get(p + "mlp.up.weight", I * D, tu)) return st;
+      if (cs_status st = wb.get(p + "mlp.gate.bias", I, bg, true)) return st;
+      if (cs_status st = wb.get(p + "mlp.up.bias", I, bu, true)) return st;
+      const int64_t Ip = e->I_pad;
+      L.w1 = A.alloc((size_t)2 * Ip * D * 2);
+      L.b1 = A.alloc((size_t)2 * Ip * 4);
+      for (int64_t r = 0; r < 2 * Ip; ++r) {
+        const int64_t blk = r / 64, in = r % 64;
+        const int64_t j = blk * 32 + (in & 31);
+        if (j >= I) continue;
+        const SrcTensor& w = in < 32 ? tg : tu;
+        const SrcTensor& bb = in < 32 ? bg : bu;
+        bf16_t* d = A.bf(L.w1) + r * D;
+        for (int64_t k = 0; k < D; ++k) d[k] = w.bits(j * D + k);
+        if (bb.data) A.f32(L.b1)[r] = bb.at(j);
+      }
+      if (cs_status st = wb.get(p + "mlp.down.weight", D * I, t)) return st;
+      if (cs_status st = wb.get(p + "mlp.down.bias", D, b, true)) return st;
+      L.w2 = pack_matrix(A, t, D, I, Ip, ident);
+      L.b2 = pack_vector(A, b, D, ident);
+    } else {
+      const int64_t Ip = e->I_pad;
+      if (cs_status st = wb.get(p + "mlp.fc1.weight", I * D, t)) return st;
+      if (cs_status st = wb.get(p + "mlp.fc1.bias", I, b, true)) return st;
+      L.w1 = pack_matrix(A, t, Ip, D, D, [&](int64_t r) { return r < I ? r : -1; });
+      L.b1 = pack_vector(A, b, Ip, [&](int64_t r) { return r < I ? r : -1; });
+      if (cs_status st = wb.get(p + "mlp.fc2.weight", D * I, t)) return st;
+      if (cs_status st = wb.get(p + "mlp.fc2.bias", D, b, true)) return st;
+      L.w2 = pack_matrix(A, t, D, I, Ip, ident);
+      L.b2 = pack_vector(A, b, D, ident);
+    }
+  }
+  if (c.arch == CS_ARCH_VIT) {
+    const int64_t P = c.patch_dim, G = (int64_t)c.merge * c.merge * D, MH = c.merger_hidden, H = c.out_hidden;
+    if (cs_status st = wb.get("patch_embed.weight", D * P, t)) return st;
+    e->w_pe = pack_matrix(A, t, D, P, e->P_pad, ident);
+    if (cs_status st = wb.get("merger.norm.weight", D, t)) return st;
+    e->g_m = pack_vector(A, t, D, ident);
+    if (cs_status st = wb.get("merger.fc1.weight", MH * G, t)) return st;
+    if (cs_status st = wb.get("merger.fc1.bias", MH, b, true)) return st;
+    e->w_m1 = pack_matrix(A, t, e->MH_pad, G, G, [&](int64_t r) { return r < MH ? r : -1; });
+    e->b_m1 = pack_vector(A, b, e->MH_pad, [&](int64_t r) { return r < MH ? r : -1; });
+    if (cs_status st = wb.get("merger.fc2.weight", H * MH, t)) return st;
+    if (cs_status st = wb.get("merger.fc2.bias", H, b, true)) return st;
+    e->w_m2 = pack_matrix(A, t, H, MH, e->MH_pad, ident);
+    e->b_m2 = pack_vector(A, b, H, ident);
+    // rotary: per pair j the axis it follows and its inverse frequency
+    e->inv_freq = A.alloc((size_t)std::max(e->half, 1) * 4);
+    e->axis = A.alloc((size_t)std::max(e->half, 1) * 4);
+    if (e->rope) {
+      int j = 0;
+      for (int a = 0; a < 3; ++a)
+        for (int i = 0; i < c.rope_sections[a]; ++i, ++j) {
+          A.f32(e->inv_freq)[j] = (float)pow((double)c.rope_theta, -(double)i / c.rope_sections[a]);
+          reinterpret_cast<int32_t*>(A.host.data() + e->axis)[j] = a;
+        }
+    }
+  } else {
+    const int64_t C = c.patch_dim, H = c.out_hidden;
+    // conv weight [out, in, 3] -> [out, 3*in] with column d*in + c (tap-major), matching an input row
+    // made of three consecutive frames
+    auto pack_conv = [&](const SrcTensor& w, int64_t cin) {
+      const size_t off = A.alloc((size_t)D * 3 * cin * 2);
+      for (int64_t o = 0; o < D; ++o)
+        for (int64_t d = 0; d < 3; ++d)
+          for (int64_t ci = 0; ci < cin; ++ci) A.bf(off)[(o * 3 + d) * cin + ci] = w.bits((o * cin + ci) * 3 + d);
+      return off;
+    };
+    if (cs_status st = wb.get("conv1.weight", D * C * 3, t)) return st;
+    if (cs_status st = wb.get("conv1.bias", D, b, true)) return st;
+    e->w_c1 = pack_conv(t, C);
+    e->b_c1 = pack_vector(A, b, D, ident);
+    if (cs_status st = wb.get("conv2.weight", D * D * 3, t)) return st;
+    if (cs_status st = wb.get("conv2.bias", D, b, true)) return st;
+    e->w_c2 = pack_conv(t, D);
+    e->b_c2 = pack_vector(A, b, D, ident);
+    if (cs_status st = wb.get("post.norm.weight", D, t)) return st;
+    if (cs_status st = wb.get("post.norm.bias", D, b, true)) return st;
+    e->g_p = pack_vector(A, t, D, ident);
+    e->be_p = pack_vector(A, b, D, ident);
+    if (cs_status st = wb.get("post.proj.weight", H * D, t)) return st;
+    if (cs_status st = wb.get("post.proj.bias", H, b, true)) return st;
+    e->w_p = pack_matrix(A, t, H, D, D, ident);
+    e->b_p = pack_vector(A, b, H, ident);
+    // sinusoidal positions: sin(pos w_i) | cos(pos w_i), w_i = exp(-i ln(10000)/(D/2-1))
+    e->pe_positions = 4096;
+    e->pe_tab = A.alloc((size_t)e->pe_positions * D * 4);
+    const int64_t hD = D / 2;
+    for (int64_t pos = 0; pos < e->pe_positions; ++pos)
+      for (int64_t i = 0; i < hD; ++i) {
+        const double a = (double)pos * exp(-(double)i * log(10000.0) / (double)(hD - 1));
+        A.f32(e->pe_tab)[pos * D + i] = (float)sin(a);
+        A.f32(e->pe_tab)[pos * D + hD + i] = (float)cos(a);
+      }
+  }
+  return CS_OK;
+}
+
+// ---- workspace layout -----------------------------------------------------------------------
+struct Workspace {
+  size_t plan, cos, sin, x, xn, attn, qk, vt, big, total;
+  int64_t ld_vt;
+};
+
+static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
+  const cs_encoder_config& c = e->cfg;
+  const int64_t N = p.n_tok, D = c.hidden;
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off = (size_t)round_up((int64_t)(off + bytes), 256);
+    return o;
+  };
+  w.plan = take(p.blob.size() * 4);
+  w.cos = take((size_t)N * std::max(e->half, 1) * 4);
+  w.sin = take((size_t)N * std::max(e->half, 1) * 4);
+  w.x = take((size_t)N * D * 4);
+  w.xn = take((size_t)N * D * 2);
+  w.attn = take((size_t)N * D * 2);
+  w.qk = take((size_t)N * 2 * D * 2);
+  w.ld_vt = round_up(N, 8);
+  w.vt = take((size_t)D * w.ld_vt * 2);
+  size_t big = (size_t)N * e->I_pad * 2;                                   // MLP activation
+  if (c.arch == CS_ARCH_VIT) {
+    big = std::max(big, (size_t)N * e->P_pad * 2);                          // gathered patches
+    big = std::max(big, (size_t)p.n_out * e->MH_pad * 2);                   // merger hidden
+  } else {
+    // padded mel frames, then padded conv1 output, both alive during conv1
+    big = std::max(big, (size_t)round_up(p.n_pad_rows * c.patch_dim * 2, 256) + (size_t)p.n_pad_rows * D * 2);
+  }
+  w.big = take(big);
+  w.total = off;
+  return w;
+}
+
+static cs_status make_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items, BatchPlan& p) {
+  if (e->cfg.arch == CS_ARCH_VIT) return build_vit_plan(e->cfg, cu, grid, n_items, p);
+  cs_status st = build_audio_plan(e->cfg, cu, grid, n_items, p);
+  if (st) return st;
+  for (int i = 0; i < n_items; ++i)
+    if (grid[3 * i + 2] / 2 > e->pe_positions) return fail(CS_ERR_UNSUPPORTED, "audio clip longer than the position table");
+  return CS_OK;
+}
+
+}  // namespace cs
+
+extern "C" {
+
+const char* cs_status_string(cs_status s) {
+  switch (s) {
+    case CS_OK: return "ok";
+    case CS_ERR_INVALID_ARG: return "invalid argument";
+    case CS_ERR_SHAPE: return "inconsistent shapes";
+    case CS_ERR_WORKSPACE: return "workspace too small";
+    case CS_ERR_INDEX: return "index out of range";
+    case CS_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CS_ERR_HIP: return "HIP runtime error";
+    case CS_ERR_MISSING_WEIGHT: return "missing weight";
+  }
+  return "unknown status";
+}
+
+const char* cs_last_error(void) { return g_last_error.c_str(); }
+
+cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* weights, int32_t n_weights,
+                            cs_encoder** out_encoder) {
+  if (!config || !out_encoder || (!weights && n_weights > 0) || n_weights < 0)
+    return fail(CS_ERR_INVALID_ARG, "cs_encoder_create: NULL argument");
+  *out_encoder = nullptr;
+  if (cs_status st = check_config(*config)) return st;
+  WeightBook wb;
+  wb.dtype = config->dtype;
+  for (int i = 0; i < n_weights; ++i) {
+    if (!weights[i].name || !weights[i].data || weights[i].numel <= 0)
+      return fail(CS_ERR_INVALID_ARG, "cs_encoder_create: weight entry " + std::to_string(i) + " is incomplete");
+    SrcTensor t;
+    t.data = weights[i].data;
+    t.numel = weights[i].numel;
+    t.dtype = config->dtype;
+    wb.m[weights[i].name] = t;
+  }
+  cs_encoder* e = new cs_encoder();
+  e->cfg = *config;
+  const cs_encoder_config& c = e->cfg;
+  e->P_pad = (int)round_up(c.patch_dim, 64);
+  e->I_pad = (int)round_up(c.mlp_dim, 64);
+  e->MH_pad = c.arch == CS_ARCH_VIT ? (int)round_up(c.merger_hidden, 64) : 0;
+  e->half = c.head_dim / 2;
+  e->rope = c.arch == CS_ARCH_VIT && (c.rope_sections[0] + c.rope_sections[1] + c.rope_sections[2]) > 0;
+  Arena A;
+  A.alloc(256);  // offset 0 stays unused so that 0 can mean "absent"
+  cs_status st = build_weights(e, wb, A);
+  if (st == CS_OK) {
+    hipError_t he = hipGetDevice(&e->device);
+    if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&e->dev), A.host.size());
+    if (he == hipSuccess) he = hipMemcpy(e->dev, A.host.data(), A.host.size(), hipMemcpyHostToDevice);
+    for (int s = 0; s < 2 && he == hipSuccess; ++s) he = hipEventCreateWithFlags(&e->stage_ev[s], hipEventDisableTiming);
+    if (he != hipSuccess) st = fail(CS_ERR_HIP, std::string("cs_encoder_create: ") + hipGetErrorString(he));
+    e->dev_bytes = A.host.size();
+  }
+  if (st != CS_OK) {
+    cs_encoder_destroy(e);
+    return st;
+  }
+  *out_encoder = e;
+  return CS_OK;
+}
+
+void cs_encoder_destroy(cs_encoder* e) {
+  if (!e) return;
+  if (e->dev) (void)hipFree(e->dev);
+  for (int s = 0; s < 2; ++s) {
+    if (e->stage[s]) (void)hipHostFree(e->stage[s]);
+    if (e->stage_ev[s]) (void)hipEventDestroy(e->stage_ev[s]);
+  }
+  delete e;
+}
+
+cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw, int32_t n_items,
+                           int64_t* n_out_rows, size_t* workspace_bytes) {
+  if (!enc) return fail(CS_ERR_INVALID_ARG, "cs_encoder_query: NULL encoder");
+  BatchPlan p;
+  if (cs_status st = make_plan(enc, cu_seqlens, grid_thw, n_items, p)) return st;
+  if (n_out_rows) *n_out_rows = p.n_out;
+  if (workspace_bytes) *workspace_bytes = layout_workspace(enc, p).total;
+  return CS_OK;
+}
+
+cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                         int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
+                         int32_t win_cu_capacity, int32_t* n_windows) {
+  if (!config) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: NULL config");
+  if (cs_status st = check_config(*config)) return st;
+  if (config->arch != CS_ARCH_VIT) return fail(CS_ERR_UNSUPPORTED, "cs_plan_tokens: vision encoders only");
+  BatchPlan p;
+  if (cs_status st = build_vit_plan(*config, cu_seqlens, grid_thw, n_items, p)) return st;
+  if (src_row) memcpy(src_row, p.blob.data() + p.off_src_row, (size_t)p.n_tok * 4);
+  if (out_row) memcpy(out_row, p.blob.data() + p.off_out_row, (size_t)p.n_out * 4);
+  const int32_t nw = (int32_t)p.win_cu.size() - 1;
+  if (n_windows) *n_windows = nw;
+  if (win_cu) {
+    if (win_cu_capacity < nw + 1) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: win_cu_capacity too small");
+    memcpy(win_cu, p.win_cu.data(), (size_t)(nw + 1) * 4);
+  }
+  return CS_OK;
+}
+
+cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                    int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes, void* stream_) {
+  if (!e || !patches || !out_embeddings || !workspace) return fail(CS_ERR_INVALID_ARG, "cs_encode: NULL argument");
+  if ((reinterpret_cast<uintptr_t>(patches) | reinterpret_cast<uintptr_t>(out_embeddings) |
+       reinterpret_cast<uintptr_t>(workspace)) & 15)
+    return fail(CS_ERR_INVALID_ARG, "cs_encode: device pointers must be 16-byte aligned");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const cs_encoder_config& c = e->cfg;
+  BatchPlan p;
+  if (cs_status st = make_plan(e, cu_seqlens, grid_thw, n_items, p)) return st;
+  const Workspace w = layout_workspace(e, p);
+  if (workspace_bytes < w.total)
+    return fail(CS_ERR_WORKSPACE, "cs_encode: workspace has " + std::to_string(workspace_bytes) + " bytes, needs " +
+                                      std::to_string(w.total));
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+
+  // ---- index tables: host -> pinned slot -> workspace, one async copy
+  {
+    const int s = e->stage_next;
+    e->stage_next ^= 1;
+    const size_t bytes = p.blob.size() * 4;
+    if (e->stage_used[s]) CS_HIP(hipEventSynchronize(e->stage_ev[s]));  // the copy that last read this slot is done
+    if (e->stage_cap[s] < bytes) {
+      if (e->stage[s]) CS_HIP(hipHostFree(e->stage[s]));
+      e->stage[s] = nullptr;
+      e->stage_cap[s] = 0;
+      CS_HIP(hipHostMalloc(&e->stage[s], bytes + bytes / 2, hipHostMallocDefault));
+      e->stage_cap[s] = bytes + bytes / 2;
+    }
+    memcpy(e->stage[s], p.blob.data(), bytes);
+    CS_HIP(hipMemcpyAsync(ws + w.plan, e->stage[s], bytes, hipMemcpyHostToDevice, stream));
+    CS_HIP(hipEventRecord(e->stage_ev[s], stream));
+    e->stage_used[s] = true;
+  }
+  const int32_t* plan = reinterpret_cast<const int32_t*>(ws + w.plan);
+  const int64_t N = p.n_tok, D = c.hidden;
+  float* x = reinterpret_cast<float*>(ws + w.x);
+  bf16_t* xn = reinterpret_cast<bf16_t*>(ws + w.xn);
+  bf16_t* attn = reinterpret_cast<bf16_t*>(ws + w.attn);
+  bf16_t* qk = reinterpret_cast<bf16_t*>(ws + w.qk);
+  bf16_t* vt = reinterpret_cast<bf16_t*>(ws + w.vt);
+  bf16_t* big = reinterpret_cast<bf16_t*>(ws + w.big);
+  float* rcos = reinterpret_cast<float*>(ws + w.cos);
+  float* rsin = reinterpret_cast<float*>(ws + w.sin);
+  const bool vit = c.arch == CS_ARCH_VIT;
+  const int out_epi = c.out_dtype == CS_BF16 ? EPI_BF16 : EPI_F32;
+
+  auto gemm = [&](int epi, const bf16_t* A, int64_t lda, size_t W, size_t bias, void* out, int64_t ldo, int64_t M,
+                  int64_t Nn, int64_t K, const int32_t* row_map) {
+    GemmArgs g = {};
+    g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.bias = bias ? e->ptr<float>(bias) : nullptr;
+    g.out = out; g.ldo = ldo; g.row_map = row_map; g.M = (int32_t)M; g.N = (int32_t)Nn; g.K = (int32_t)K;
+    return launch_gemm(epi, g, stream);
+  };
+
+  // ---- front end: tokens into the fp32 residual stream x [N, D]
+  if (vit) {
+    if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, c.patch_dim, plan + p.off_src_row, big, e->P_pad, N, stream)) return st;
+    if (e->rope)
+      if (cs_status st = launch_rope_table(plan + p.off_pos, e->ptr<int32_t>(e->axis), e->ptr<float>(e->inv_freq), e->half, rcos, rsin, N, stream)) return st;
+    if (cs_status st = gemm(EPI_F32, big, e->P_pad, e->w_pe, 0, x, D, N, D, e->P_pad, nullptr)) return st;
+  } else {
+    const int64_t R = p.n_pad_rows, C = c.patch_dim;
+    bf16_t* melp = big;
+    bf16_t* c1buf = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(big) + round_up(R * C * 2, 256));
+    if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, (int32_t)C, plan + p.off_mel_src, melp, (int32_t)C, R, stream)) return st;
+    if (cs_status st = launch_zero_rows(c1buf, plan + p.off_zero_rows, p.n_zero_rows, (int32_t)D, stream)) return st;
+    if (cs_status st = gemm(EPI_GELU_BF16, melp, C, e->w_c1, e->b_c1, c1buf, D, R - 2, D, 3 * C, plan + p.off_c1_map)) return st;
+    if (cs_status st = gemm(EPI_GELU_F32, c1buf, 2 * D, e->w_c2, e->b_c2, x, D, R / 2 - 1, D, 3 * D, plan + p.off_c2_map)) return st;
+    if (cs_status st = launch_add_rows(x, e->ptr<float>(e->pe_tab), plan + p.off_pos, N, (int32_t)D, stream)) return st;
+  }
+
+  // ---- transformer blocks
+  AttnArgs aa = {};
+  aa.qk = qk; aa.vt = vt; aa.ld_vt = w.ld_vt; aa.out = attn; aa.n_tok = (int32_t)N; aa.n_heads = c.n_heads; aa.head_dim = c.head_dim;
+  const float q_scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& L = e->layers[l];
+    if (vit) { if (cs_status st = launch_rmsnorm(x, e->ptr<float>(L.g1), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
+    else { if (cs_status st = launch_layernorm(x, e->ptr<float>(L.g1), e->ptr<float>(L.be1), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
+    {
+      GemmArgs g = {};
+      g.A = xn; g.lda = D; g.W = e->ptr<bf16_t>(L.wqkv); g.bias = e->ptr<float>(L.bqkv);
+      g.out = qk; g.ldo = 2 * D; g.M = (int32_t)N; g.N = (int32_t)(3 * D); g.K = (int32_t)D;
+      g.vt = vt; g.ld_vt = w.ld_vt; g.rope_cos = e->rope ? rcos : nullptr; g.rope_sin = e->rope ? rsin : nullptr;
+      g.hidden = (int32_t)D; g.head_dim = c.head_dim; g.q_scale = q_scale;
+      if (cs_status st = launch_gemm(EPI_QKV, g, stream)) return st;
+    }
+    const bool full = !vit || c.window <= 0 || ((c.full_attn_layer_mask >> l) & 1);
+    if (full) {
+      aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256;
+    } else {
+      aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64;
+    }
+    if (cs_status st = launch_attention(aa, stream)) return st;
+    if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st;
+    if (vit) { if (cs_status st = launch_rmsnorm(x, e->ptr<float>(L.g2), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
+    else { if (cs_status st = launch_layernorm(x, e->ptr<float>(L.g2), e->ptr<float>(L.be2), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
+    if (vit) { if (cs_status st = gemm(EPI_SWIGLU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, 2 * e->I_pad, D, nullptr)) return st; }
+    else { if (cs_status st = gemm(EPI_GELU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, e->I_pad, D, nullptr)) return st; }
+    if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st;
+  }
+
+  // ---- back end: merged / pooled tokens -> embedding rows
+  if (vit) {
+    const int64_t M = p.n_out, G = (int64_t)c.merge * c.merge * D;
+    if (cs_status st = launch_rmsnorm(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, stream)) return st;
+    if (cs_status st = gemm(EPI_GELU_BF16, xn, G, e->w_m1, e->b_m1, big, e->MH_pad, M, e->MH_pad, G, nullptr)) return st;
+    if (cs_status st = gemm(out_epi, big, e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, e->MH_pad, plan + p.off_out_row)) return st;
+  } else {
+    if (cs_status st = launch_pool_layernorm(x, e->ptr<float>(e->g_p), e->ptr<float>(e->be_p), c.norm_eps, xn, p.n_out, (int32_t)D, c.merge, stream)) return st;
+    if (cs_status st = gemm(out_epi, xn, D, e->w_p, e->b_p, out_embeddings, c.out_hidden, p.n_out, c.out_hidden, D, nullptr)) return st;
+  }
+  return CS_OK;
+}
+
+cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_index, void* dst_seq, int64_t n_rows,
+                                int64_t dst_rows, int32_t hidden, int32_t dtype, int32_t* err_flag, void* stream) {
+  if (n_rows < 0 || dst_rows < 0 || hidden <= 0) return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: negative size");
+  if (dtype != CS_F32 && dtype != CS_BF16) return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: dtype");
+  if (n_rows == 0) return CS_OK;
+  if (!src || !placeholder_index || !dst_seq) return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: NULL argument");
+  const int64_t row_bytes = (int64_t)hidden * (dtype == CS_BF16 ? 2 : 4);
+  if (row_bytes % 16) return fail(CS_ERR_UNSUPPORTED, "cs_forward_embeddings: a row must be a multiple of 16 bytes");
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst_seq)) & 15)
+    return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: src and dst_seq must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(placeholder_index) & 7) || (reinterpret_cast<uintptr_t>(err_flag) & 3))
+    return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: misaligned index or flag pointer");
+  return launch_scatter_rows(src, placeholder_index, dst_seq, n_rows, dst_rows, row_bytes, err_flag,
+                             static_cast<hipStream_t>(stream));
+}
+
+cs_status cs_linear_bf16(const void* A, int64_t lda, const void* W, const float* bias, void* C, int32_t c_dtype,
+                         int64_t M, int32_t N, int32_t K, void* stream) {
+  if (!A || !W || !C) return fail(CS_ERR_INVALID_ARG, "cs_linear_bf16: NULL argument");
+  if (M < 0 || M > 0x7fffffff || N < 0) return fail(CS_ERR_INVALID_ARG, "cs_linear_bf16: sizes");
+  GemmArgs g = {};
+  g.A = static_cast<const bf16_t*>(A); g.lda = lda; g.W = static_cast<const bf16_t*>(W); g.bias = bias;
+  g.out = C; g.ldo = N; g.M = (int32_t)M; g.N = N; g.K = K;
+  return launch_gemm(c_dtype == CS_BF16 ? EPI_BF16 : EPI_F32, g, static_cast<hipStream_t>(stream));
+}
+
+cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
+                              int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream_) {
+  if (!qk || !vt || !out || !seg_cu || n_seg <= 0) return fail(CS_ERR_INVALID_ARG, "cs_attention_varlen: NULL argument");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  std::vector<int32_t> work;
+  int max_len = 0;
+  for (int s = 0; s < n_seg; ++s) {
+    if (seg_cu[s] % 4 || seg_cu[s + 1] <= seg_cu[s]) return fail(CS_ERR_SHAPE, "cs_attention_varlen: segment boundaries");
+    max_len = std::max(max_len, seg_cu[s + 1] - seg_cu[s]);
+  }
+  const int qpb = max_len <= 64 ? 64 : 256;
+  for (int s = 0; s < n_seg; ++s)
+    for (int q = seg_cu[s]; q < seg_cu[s + 1]; q += qpb) {
+      work.push_back(q); work.push_back(std::min(q + qpb, seg_cu[s + 1])); work.push_back(seg_cu[s]); work.push_back(seg_cu[s + 1]);
+    }
+  // component call for tests and micro-benchmarks: the work list is uploaded synchronously
+  AttnWork* dwork = nullptr;
+  CS_HIP(hipMalloc(reinterpret_cast<void**>(&dwork), work.size() * 4));
+  hipError_t he = hipMemcpy(dwork, work.data(), work.size() * 4, hipMemcpyHostToDevice);
+  cs_status st = CS_OK;
+  if (he != hipSuccess) st = fail(CS_ERR_HIP, hipGetErrorString(he));
+  if (st == CS_OK) {
+    AttnArgs a = {};
+    a.qk = static_cast<const bf16_t*>(qk); a.vt = static_cast<const bf16_t*>(vt); a.ld_vt = ld_vt;
+    a.out = static_cast<bf16_t*>(out); a.work = dwork; a.n_work = (int32_t)(work.size() / 4);
+    a.n_tok = seg_cu[n_seg]; a.n_heads = n_heads; a.head_dim = head_dim; a.q_per_block = qpb;
+    st = launch_attention(a, stream);
+    (void)hipStreamSynchronize(stream);
+  }
+  (void)hipFree(dwork);
+  return st;
+}
+
+}  // extern "C"

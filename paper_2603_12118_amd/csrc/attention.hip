@@ -1,0 +1,210 @@
+// Variable-length attention for gfx950, one kernel for window layers and full layers.
+//
+// A work item names a block of queries [q0,q1) and the keys [kv0,kv1) they attend to (both in
+// token indices of the packed batch); a window layer has one item per window, a full layer
+// cuts every sequence into query blocks.  Inside a workgroup every wave owns 64 queries and
+// all waves walk the same 64-key tiles, which are staged in LDS once per workgroup.
+//
+// Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then holds
+// one query column (lane % 32) and 16 of the 32 key rows of a tile, so the online-softmax state
+// (running max, running sum, rescale factor) is per lane, and the exponentiated scores are
+// already laid out as the B operand of the second product O^T = V^T P^T.  V is consumed
+// transposed (token-contiguous), which is how the QKV projection stores it.  q arrives
+// pre-multiplied by softmax_scale * log2(e); probabilities are exp2 of score differences.
+#include "common.h"
+
+namespace cs {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t f2bf_a(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+template <int DH, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
+  constexpr int NT = 64 * NW;
+  constexpr int KS = DH / 16;            // k-steps of the score product
+  constexpr int DT = (DH + 31) / 32;     // 32-row tiles of O^T
+  constexpr int KSTR = DH * 2 + 16;      // LDS row stride of the K tile, bytes
+  constexpr int VSTR = 64 * 2 + 8;       // LDS row stride of the V^T tile, bytes
+  constexpr int KCH = DH / 8;            // 16-byte chunks per K row
+  __shared__ __align__(16) unsigned char k_lds[64 * KSTR];
+  __shared__ __align__(16) unsigned char v_lds[DT * 32 * VSTR];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lhi = lane >> 5;
+  const AttnWork w = a.work[blockIdx.x];
+  const int head = blockIdx.y;
+  const int hidden = a.n_heads * DH;
+  const int64_t ldq = 2 * (int64_t)hidden;
+  const bf16_t* qbase = a.qk + head * DH;
+  const bf16_t* kbase = a.qk + hidden + head * DH;
+  const bf16_t* vbase = a.vt + (int64_t)head * DH * a.ld_vt;
+  const int last_tok = a.n_tok - 1;
+
+  // ---- this wave's queries as B operands: lane = query column, 8 consecutive dims per k-step
+  const int qw = w.q0 + wave * 64;
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    int row = qw + it * 32 + l31;
+    row = row < last_tok ? row : last_tok;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      qf[it][ks] = *reinterpret_cast<const bf16x8*>(qbase + (int64_t)row * ldq + ks * 16 + lhi * 8);
+  }
+
+  f32x16 o[2][DT];
+#pragma unroll
+  for (int it = 0; it < 2; ++it)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[it][dt][r] = 0.f;
+  float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
+
+  for (int kv = w.kv0; kv < w.kv1; kv += 64) {
+    __syncthreads();  // previous tile fully consumed
+    // ---- stage K tile [64 keys][DH] and V^T tile [DH][64 keys]
+    for (int c = tid; c < 64 * KCH; c += NT) {
+      const int r = c / KCH, ch = c % KCH;
+      int row = kv + r;
+      row = row < last_tok ? row : last_tok;
+      const uint4 val = *reinterpret_cast<const uint4*>(kbase + (int64_t)row * ldq + ch * 8);
+      *reinterpret_cast<uint4*>(k_lds + r * KSTR + ch * 16) = val;
+    }
+    for (int c = tid; c < DH * 16; c += NT) {
+      const int d = c >> 4, ch = c & 15;
+      int tok = kv + ch * 4;
+      tok = tok < a.n_tok - 4 ? tok : a.n_tok - 4;   // n_tok is a multiple of 4
+      const uint2 val = *reinterpret_cast<const uint2*>(vbase + (int64_t)d * a.ld_vt + tok);
+      *reinterpret_cast<uint2*>(v_lds + d * VSTR + ch * 8) = val;
+    }
+    __syncthreads();
+
+    // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
+    f32x16 s[2][2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[it][jt][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + (jt * 32 + l31) * KSTR + ks * 32 + lhi * 16);
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+          s[it][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[it][ks], s[it][jt], 0, 0, 0);
+      }
+    }
+    // register r of a tile holds key row 8*(r/4) + 4*lhi + r%4
+    if (kv + 64 > w.kv1) {
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv + jt * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
+          if (key >= w.kv1) {
+            s[0][jt][r] = -INFINITY;
+            s[1][jt][r] = -INFINITY;
+          }
+        }
+    }
+    // ---- online softmax, per query column
+    bf16x8 pf[2][4];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      float mx = s[it][0][0];
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[it][jt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = fmaxf(mrun[it], mx);      // finite: every tile holds at least one valid key
+      const float alpha = exp2f(mrun[it] - mnew);
+      mrun[it] = mnew;
+      float sum = 0.f;
+#pragma unroll
+      for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          uint32_t pk[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p0 = exp2f(s[it][jt][8 * u + 2 * e] - mnew);
+            const float p1 = exp2f(s[it][jt][8 * u + 2 * e + 1] - mnew);
+            sum += p0 + p1;
+            pk[e] = f2bf_a(p0) | (f2bf_a(p1) << 16);
+          }
+          uint4 t = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+          pf[it][jt * 2 + u] = *reinterpret_cast<bf16x8*>(&t);
+        }
+      lrun[it] = lrun[it] * alpha + sum;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[it][dt][r] *= alpha;
+    }
+    // ---- O^T += V^T P^T.  k-slot e of lane-half lhi in step (jt,u) is key jt*32 + 16u + 8*(e/4) + 4*lhi + e%4
+#pragma unroll
+    for (int ku = 0; ku < 4; ++ku) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const unsigned char* vp = v_lds + (dt * 32 + l31) * VSTR + (ku * 16 + 4 * lhi) * 2;
+        uint4 t;
+        const uint2 lo = *reinterpret_cast<const uint2*>(vp);
+        const uint2 hi = *reinterpret_cast<const uint2*>(vp + 16);
+        t.x = lo.x; t.y = lo.y; t.z = hi.x; t.w = hi.y;
+        const bf16x8 vf = *reinterpret_cast<bf16x8*>(&t);
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+          o[it][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[it][ku], o[it][dt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- normalise and store: register r of o[it][dt] is dim dt*32 + 8*(r/4) + 4*lhi + r%4 of query it*32 + lane%32
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const float l = lrun[it] + __shfl_xor(lrun[it], 32);
+    const float inv = 1.0f / l;
+    const int q = qw + it * 32 + l31;
+    if (q >= w.q1) continue;
+    bf16_t* orow = a.out + (int64_t)q * hidden + head * DH;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int d = dt * 32 + 8 * g + 4 * lhi;
+        if (d < DH) {
+          uint2 pk;
+          pk.x = f2bf_a(o[it][dt][4 * g + 0] * inv) | (f2bf_a(o[it][dt][4 * g + 1] * inv) << 16);
+          pk.y = f2bf_a(o[it][dt][4 * g + 2] * inv) | (f2bf_a(o[it][dt][4 * g + 3] * inv) << 16);
+          *reinterpret_cast<uint2*>(orow + d) = pk;
+        }
+      }
+  }
+}
+
+cs_status launch_attention(const AttnArgs& a, hipStream_t stream) {
+  if (a.n_work <= 0) return CS_OK;
+  if (a.n_tok < 4 || (a.n_tok & 3)) return fail(CS_ERR_UNSUPPORTED, "attention: token count must be a multiple of 4");
+  if (a.ld_vt & 3) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt must be a multiple of 4");
+  dim3 grid(a.n_work, a.n_heads);
+  if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 1>), grid, dim3(64), 0, stream, a);
+  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 4>), grid, dim3(256), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 1>), grid, dim3(64), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 4>), grid, dim3(256), 0, stream, a);
+  else return fail(CS_ERR_UNSUPPORTED, "attention: head_dim must be 64 or 80 and q_per_block 64 or 256");
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+}  // namespace cs

@@ -1,0 +1,95 @@
+// Shared declarations of the library's translation units (host side + kernel launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "../../include/cornenc.h"
+
+namespace cs {
+
+typedef uint16_t bf16_t;  // raw bf16 storage word
+
+// ---- error plumbing -------------------------------------------------------------------
+void set_error(const std::string& msg);
+cs_status fail(cs_status s, const std::string& msg);
+
+#define CS_HIP(expr)                                                                          \
+  do {                                                                                        \
+    hipError_t _e = (expr);                                                                   \
+    if (_e != hipSuccess)                                                                     \
+      return ::cs::fail(CS_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(_e));       \
+  } while (0)
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---- GEMM  C = epilogue(A W^T) ----------------------------------------------------------
+enum GemmEpilogue {
+  EPI_BF16 = 0,       // (acc + bias) -> bf16
+  EPI_F32 = 1,        // (acc + bias) -> fp32
+  EPI_GELU_BF16 = 2,  // gelu(acc + bias) -> bf16
+  EPI_GELU_F32 = 3,   // gelu(acc + bias) -> fp32
+  EPI_RESADD_F32 = 4, // out += acc + bias   (fp32 residual stream)
+  EPI_SWIGLU_BF16 = 5,// weight rows interleaved in blocks of 32: gate | up; out[:, j] = silu(g) * u
+  EPI_QKV = 6         // q,k: bias, rotary, (q: scale) -> bf16 row-major; v: bias -> bf16 transposed
+};
+
+struct GemmArgs {
+  const bf16_t* A;   // [M, lda]
+  int64_t lda;
+  const bf16_t* W;   // [N, K], K % 64 == 0
+  const float* bias; // [N] or nullptr
+  void* out;         // [*, ldo]
+  int64_t ldo;
+  const int32_t* row_map;  // nullptr, or destination row per m (negative: skip)
+  int32_t M, N, K;
+  // EPI_QKV only
+  bf16_t* vt;        // [hidden, ld_vt]
+  int64_t ld_vt;
+  const float* rope_cos;   // [M, head_dim/2] or nullptr (no rotary)
+  const float* rope_sin;
+  int32_t hidden;    // q columns [0,hidden), k [hidden,2 hidden), v [2 hidden, 3 hidden)
+  int32_t head_dim;
+  float q_scale;
+};
+
+cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
+
+// ---- attention ------------------------------------------------------------------------------
+struct AttnWork {  // one workgroup: queries [q0,q1) against keys [kv0,kv1), token indices
+  int32_t q0, q1, kv0, kv1;
+};
+struct AttnArgs {
+  const bf16_t* qk;   // [n_tok, 2*hidden]
+  const bf16_t* vt;   // [hidden, ld_vt]
+  int64_t ld_vt;
+  bf16_t* out;        // [n_tok, hidden]
+  const AttnWork* work;
+  int32_t n_work, n_tok, n_heads, head_dim;
+  int32_t q_per_block;  // 64 or 256 queries per workgroup (work items are cut accordingly)
+};
+cs_status launch_attention(const AttnArgs& a, hipStream_t stream);
+
+// ---- row-wise and copy kernels ----------------------------------------------------------
+cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                         hipStream_t s);
+cs_status launch_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
+                           int64_t rows, int32_t dim, hipStream_t s);
+// y[r] = layernorm(mean of `pool` consecutive rows of x)
+cs_status launch_pool_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
+                                int64_t out_rows, int32_t dim, int32_t pool, hipStream_t s);
+// dst[r, 0:dst_cols) = bf16(src[src_row[r], 0:src_cols)) padded with zeros; src_row < 0 gives a zero row
+cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols, const int32_t* src_row,
+                             bf16_t* dst, int32_t dst_cols, int64_t rows, hipStream_t s);
+// cos/sin[n, j] of pos[n, axis[j]] * inv_freq[j]
+cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half,
+                            float* cos_out, float* sin_out, int64_t n_tok, hipStream_t s);
+// x[r, :] += table[pos[r], :]
+cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim,
+                          hipStream_t s);
+cs_status launch_zero_rows(bf16_t* buf, const int32_t* rows, int32_t n_rows, int32_t cols, hipStream_t s);
+cs_status launch_scatter_rows(const void* src, const int64_t* index, void* dst, int64_t n_rows, int64_t dst_rows,
+                              int64_t row_bytes, int32_t* err_flag, hipStream_t s);
+
+}  // namespace cs

@@ -1,0 +1,260 @@
+// Bandwidth-bound kernels: normalisations, input gather/cast, rotary table, position add and the
+// embedding hand-off (row scatter).  All are one pass over HBM with 16-byte (or 8-byte) accesses.
+#include "common.h"
+
+namespace cs {
+
+__device__ __forceinline__ uint32_t f2bf_e(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+constexpr int NORM_MAX_V4 = 8;  // a wave keeps a row of up to 64*4*8 = 2048 floats in registers
+
+// One wave per row.  MODE 0: RMSNorm.  MODE 1: LayerNorm.  POOL rows of x are averaged first.
+template <int MODE>
+__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                   const float* __restrict__ bias, float eps,
+                                                   bf16_t* __restrict__ y, int64_t rows, int dim, int pool) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  float4 v[NORM_MAX_V4];
+  const int nv = dim >> 2;
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    const int c = lane + 64 * i;
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < nv) {
+      for (int p = 0; p < pool; ++p) {
+        const float4 t = reinterpret_cast<const float4*>(x + (row * pool + p) * dim)[c];
+        v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+      }
+      if (pool > 1) {
+        const float ip = 1.0f / pool;
+        v[i].x *= ip; v[i].y *= ip; v[i].z *= ip; v[i].w *= ip;
+      }
+    }
+  }
+  float mean = 0.f;
+  if (MODE == 1) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NORM_MAX_V4; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    mean = wave_sum(s) / dim;
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    if (lane + 64 * i < nv) {
+      const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      ss += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(ss) / dim + eps);
+#pragma unroll
+  for (int i = 0; i < NORM_MAX_V4; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nv) {
+      const float4 g = reinterpret_cast<const float4*>(gain)[c];
+      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (MODE == 1) b = reinterpret_cast<const float4*>(bias)[c];
+      const float o0 = (v[i].x - mean) * rstd * g.x + b.x, o1 = (v[i].y - mean) * rstd * g.y + b.y;
+      const float o2 = (v[i].z - mean) * rstd * g.z + b.z, o3 = (v[i].w - mean) * rstd * g.w + b.w;
+      uint2 pk;
+      pk.x = f2bf_e(o0) | (f2bf_e(o1) << 16);
+      pk.y = f2bf_e(o2) | (f2bf_e(o3) << 16);
+      reinterpret_cast<uint2*>(y + row * dim)[c] = pk;
+    }
+  }
+}
+
+static cs_status norm_check(int64_t rows, int dim) {
+  if (dim <= 0 || (dim & 3) || dim > 64 * 4 * NORM_MAX_V4)
+    return fail(CS_ERR_UNSUPPORTED, "norm: dim must be a multiple of 4, at most 2048");
+  if (rows > (int64_t)4 * 0x7fffffff) return fail(CS_ERR_UNSUPPORTED, "norm: too many rows");
+  return CS_OK;
+}
+
+cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                         hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (cs_status st = norm_check(rows, dim)) return st;
+  hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
+                     rows, dim, 1);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+cs_status launch_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y, int64_t rows,
+                           int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (cs_status st = norm_check(rows, dim)) return st;
+  hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y, rows,
+                     dim, 1);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+cs_status launch_pool_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
+                                int64_t out_rows, int32_t dim, int32_t pool, hipStream_t s) {
+  if (out_rows <= 0) return CS_OK;
+  if (cs_status st = norm_check(out_rows, dim)) return st;
+  if (pool < 1) return fail(CS_ERR_INVALID_ARG, "pool_layernorm: pool < 1");
+  hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y,
+                     out_rows, dim, pool);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- gather + cast to bf16 with zero padding; 4 elements per thread
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void gather_cast_kernel(const void* __restrict__ src, int src_cols,
+                                                          const int32_t* __restrict__ src_row,
+                                                          bf16_t* __restrict__ dst, int dst_cols, int64_t rows) {
+  const int cpr = dst_cols >> 2;
+  const int64_t total = rows * cpr;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / cpr;
+    const int c = (int)(t - r * cpr) * 4;
+    const int64_t sr = src_row ? src_row[r] : r;
+    uint2 pk = make_uint2(0u, 0u);
+    if (sr >= 0 && c < src_cols) {
+      if (SRC_BF16) {
+        pk = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(src) + sr * src_cols + c);
+      } else {
+        const float4 v = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + sr * src_cols + c);
+        pk.x = f2bf_e(v.x) | (f2bf_e(v.y) << 16);
+        pk.y = f2bf_e(v.z) | (f2bf_e(v.w) << 16);
+      }
+    }
+    *reinterpret_cast<uint2*>(dst + r * dst_cols + c) = pk;
+  }
+}
+
+cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols, const int32_t* src_row, bf16_t* dst,
+                             int32_t dst_cols, int64_t rows, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if ((src_cols & 3) || (dst_cols & 3) || dst_cols < src_cols)
+    return fail(CS_ERR_UNSUPPORTED, "gather_cast: column counts must be multiples of 4, dst >= src");
+  const int64_t total = rows * (dst_cols >> 2);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
+  if (src_is_bf16)
+    hipLaunchKernelGGL(gather_cast_kernel<true>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows);
+  else
+    hipLaunchKernelGGL(gather_cast_kernel<false>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- rotary cos/sin table
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos, const int32_t* __restrict__ axis,
+                                                         const float* __restrict__ inv_freq, int half,
+                                                         float* __restrict__ cos_out, float* __restrict__ sin_out,
+                                                         int64_t total) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= total) return;
+  const int64_t n = t / half;
+  const int j = (int)(t - n * half);
+  const float ang = (float)pos[n * 3 + axis[j]] * inv_freq[j];
+  float sn, cs_;
+  sincosf(ang, &sn, &cs_);
+  cos_out[t] = cs_;
+  sin_out[t] = sn;
+}
+
+cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half, float* cos_out,
+                            float* sin_out, int64_t n_tok, hipStream_t s) {
+  const int64_t total = n_tok * half;
+  if (total <= 0) return CS_OK;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pos, axis, inv_freq, half,
+                     cos_out, sin_out, total);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- x[r,:] += table[pos[r],:]
+__global__ __launch_bounds__(256) void add_rows_kernel(float* __restrict__ x, const float* __restrict__ table,
+                                                       const int32_t* __restrict__ pos, int64_t rows, int dim) {
+  const int cpr = dim >> 2;
+  const int64_t total = rows * cpr;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / cpr;
+    const int c = (int)(t - r * cpr);
+    float4 v = reinterpret_cast<float4*>(x + r * dim)[c];
+    const float4 p = reinterpret_cast<const float4*>(table + (int64_t)pos[r] * dim)[c];
+    v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    reinterpret_cast<float4*>(x + r * dim)[c] = v;
+  }
+}
+
+cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (dim & 3) return fail(CS_ERR_UNSUPPORTED, "add_rows: dim must be a multiple of 4");
+  const int64_t total = rows * (dim >> 2);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
+  hipLaunchKernelGGL(add_rows_kernel, dim3(blocks), dim3(256), 0, s, x, table, pos, rows, dim);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- embedding hand-off: dst[index[i], :] = src[i, :], 16 bytes per thread, rows whole
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ src, const int64_t* __restrict__ index,
+                                                           uint4* __restrict__ dst, int64_t n_rows, int64_t dst_rows,
+                                                           int chunks_per_row, int32_t* err_flag) {
+  const int64_t total = n_rows * chunks_per_row;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / chunks_per_row;
+    const int c = (int)(t - r * chunks_per_row);
+    const int64_t d = index[r];
+    if (d == -1) continue;
+    if (d < -1 || d >= dst_rows) {
+      if (err_flag && c == 0) *err_flag = 1;
+      continue;
+    }
+    dst[d * chunks_per_row + c] = src[t];
+  }
+}
+
+cs_status launch_scatter_rows(const void* src, const int64_t* index, void* dst, int64_t n_rows, int64_t dst_rows,
+                              int64_t row_bytes, int32_t* err_flag, hipStream_t s) {
+  if (n_rows <= 0) return CS_OK;
+  const int64_t cpr = row_bytes >> 4;
+  const int64_t total = n_rows * cpr;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 8 ? (total + 255) / 256 : 65536 * 8);
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint4*>(src), index,
+                     static_cast<uint4*>(dst), n_rows, dst_rows, (int)cpr, err_flag);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+}  // namespace cs
+
+namespace cs {
+
+// ---- clear whole rows of a bf16 matrix (padding frames between audio clips)
+__global__ __launch_bounds__(256) void zero_rows_kernel(bf16_t* __restrict__ buf, const int32_t* __restrict__ rows,
+                                                        int n_rows, int cols) {
+  const int cpr = cols >> 3;
+  for (int t = blockIdx.x * 256 + threadIdx.x; t < n_rows * cpr; t += gridDim.x * 256) {
+    const int r = t / cpr, c = t - r * cpr;
+    reinterpret_cast<uint4*>(buf + (int64_t)rows[r] * cols)[c] = make_uint4(0u, 0u, 0u, 0u);
+  }
+}
+
+cs_status launch_zero_rows(bf16_t* buf, const int32_t* rows, int32_t n_rows, int32_t cols, hipStream_t s) {
+  if (n_rows <= 0) return CS_OK;
+  if (cols & 7) return fail(CS_ERR_UNSUPPORTED, "zero_rows: cols must be a multiple of 8");
+  const int total = n_rows * (cols >> 3);
+  hipLaunchKernelGGL(zero_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, s, buf, rows, n_rows, cols);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+}  // namespace cs

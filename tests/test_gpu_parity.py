@@ -1,0 +1,223 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU checker on the same
+seeded inputs.  Bars: bit-exact for the embedding hand-off and all index work; for embeddings
+max |gpu - oracle| <= 3e-2 and per-row cosine >= 0.999 (bf16 arithmetic against the fp64 checker
+fed the same bf16-rounded weights and inputs)."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import encoder_oracle as O
+from paper_2603_12118_amd import binding as B
+from paper_2603_12118_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+MAX_ABS, MIN_COS = 3e-2, 0.999
+
+
+def dev_bf16(x32: np.ndarray) -> torch.Tensor:
+    """fp32 array of bf16-representable values -> device bf16 tensor with the same bits."""
+    return torch.from_numpy(wl.to_bits_bf16(x32).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def dev_input(w: wl.Workload) -> torch.Tensor:
+    return dev_bf16(w.patches) if w.cfg.dtype == "bf16" else torch.from_numpy(w.patches).to(DEV)
+
+
+def check_embeddings(gpu: torch.Tensor, ref: np.ndarray, what: str):
+    g = gpu.float().cpu().numpy().astype(np.float64)
+    assert g.shape == ref.shape, (g.shape, ref.shape)
+    assert np.isfinite(g).all(), f"{what}: non-finite output"
+    err = np.abs(g - ref).max()
+    cos = (g * ref).sum(1) / (np.linalg.norm(g, axis=1) * np.linalg.norm(ref, axis=1))
+    print(f"{what}: max_abs_err={err:.4g} min_cos={cos.min():.6f} max|ref|={np.abs(ref).max():.3f}", flush=True)
+    assert err <= MAX_ABS, f"{what}: max abs error {err}"
+    assert cos.min() >= MIN_COS, f"{what}: min cosine {cos.min()}"
+
+
+# ------------------------------------------------------------------ embedding hand-off (bit-exact)
+def _scatter_case(rows, hidden, dst_rows, dtype, idx, seed=0):
+    rng = np.random.default_rng(seed)
+    if dtype == "bf16":
+        src = rng.integers(0, 1 << 16, (rows, hidden), dtype=np.uint16)
+        dst = rng.integers(0, 1 << 16, (dst_rows, hidden), dtype=np.uint16)
+        tv = lambda a: torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+        back = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    else:
+        src = rng.integers(0, 1 << 32, (rows, hidden), dtype=np.uint32)
+        dst = rng.integers(0, 1 << 32, (dst_rows, hidden), dtype=np.uint32)
+        tv = lambda a: torch.from_numpy(a.view(np.int32)).to(DEV).view(torch.float32)
+        back = lambda t: t.view(torch.int32).cpu().numpy().view(np.uint32)
+    d = tv(dst)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.cs_forward_embeddings(tv(src), torch.from_numpy(np.asarray(idx, np.int64)).to(DEV), d, err_flag=flag)
+    torch.cuda.synchronize()
+    return src, dst, back(d), int(flag.item())
+
+
+def test_forward_embeddings_c1_positions():
+    w = wl.c1_tiny()
+    src, dst, got, flag = _scatter_case(64, 512, 128, "f32", w.placeholder_index)
+    assert np.array_equal(got, O.forward_embeddings(src, w.placeholder_index, dst)) and flag == 0
+    assert np.array_equal(got[32:96], src) and np.array_equal(got[:32], dst[:32]) and np.array_equal(got[96:], dst[96:])
+
+
+@pytest.mark.parametrize("rows", [1170, 2340, 4681])       # 8, 16, 32 MB of bf16 rows, the sizes of the paper's Sec. 4.3
+def test_forward_embeddings_random_spans_bf16(rows):
+    rng = np.random.default_rng(rows)
+    dst_rows = 3 * rows + 17
+    idx = rng.permutation(dst_rows)[:rows].astype(np.int64)
+    idx[rng.integers(0, rows, 5)] = -1
+    src, dst, got, flag = _scatter_case(rows, 3584, dst_rows, "bf16", idx)
+    assert np.array_equal(got, O.forward_embeddings(src, idx, dst)) and flag == 0
+
+
+def test_forward_embeddings_edge_cases():
+    # identity index = plain copy; empty input; out-of-range index raises the flag and writes nothing
+    src, dst, got, flag = _scatter_case(33, 8, 33, "bf16", np.arange(33))
+    assert np.array_equal(got, src) and flag == 0
+    idx = np.array([2, 7, -5, 1], np.int64)
+    src, dst, got, flag = _scatter_case(4, 8, 7, "f32", idx)
+    ok = np.array([2, -1, -1, 1])
+    assert np.array_equal(got, O.forward_embeddings(src, ok, dst)) and flag == 1
+    d = torch.zeros(4, 8, device=DEV)
+    B.cs_forward_embeddings(torch.zeros(0, 8, device=DEV), torch.zeros(0, dtype=torch.int64, device=DEV), d)
+    assert B.cs_forward_embeddings_raw(1, 8, 16, 4, 4, 7, B.CS_BF16) != 0        # 14-byte rows are refused
+
+
+def test_forward_embeddings_workload_spans():
+    w = wl.c2_images(n_layers=1)
+    rows = int(w.out_rows.sum())
+    src, dst, got, flag = _scatter_case(rows, 3584, w.n_sequences * w.seq_len, "bf16", w.placeholder_index)
+    assert np.array_equal(got, O.forward_embeddings(src, w.placeholder_index, dst)) and flag == 0
+
+
+# ------------------------------------------------------------------ contraction kernels on their own
+@pytest.mark.parametrize("M,N,K", [(300, 200, 128), (1000, 520, 1216), (257, 3840, 1280), (2048, 1280, 3456)])
+def test_linear_matches_oracle(M, N, K):
+    rng = np.random.default_rng(M + N)
+    A = wl.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+    W = wl.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    b = rng.standard_normal(N).astype(np.float32)
+    ref = O.linear(A, W, b)
+    out = torch.empty(M, N, device=DEV)
+    B.cs_linear_bf16(dev_bf16(A), dev_bf16(W), torch.from_numpy(b).to(DEV), out)
+    torch.cuda.synchronize()
+    err = np.abs(out.cpu().numpy() - ref).max()
+    print(f"linear {M}x{N}x{K}: max err {err:.3g}, max|ref| {np.abs(ref).max():.3g}", flush=True)
+    assert err <= 2e-5 * math.sqrt(K) * np.abs(ref).max()       # fp32 accumulation of exact bf16 products
+    outb = torch.empty(M, N, device=DEV, dtype=torch.bfloat16)
+    B.cs_linear_bf16(dev_bf16(A), dev_bf16(W), None, outb)
+    torch.cuda.synchronize()
+    refb = O.linear(A, W)
+    assert np.abs(outb.float().cpu().numpy() - refb).max() <= 2 ** -8 * np.abs(refb).max() + 1e-6
+
+
+@pytest.mark.parametrize("dh,nh,segs", [(80, 2, [64, 16, 32, 4, 60, 64, 12]), (80, 3, [300, 1028, 64, 516]),
+                                        (64, 2, [256, 40]), (64, 1, [1500])])
+def test_attention_matches_oracle(dh, nh, segs):
+    rng = np.random.default_rng(dh + len(segs))
+    cu = np.concatenate([[0], np.cumsum(segs)])
+    n, D = int(cu[-1]), nh * dh
+    qs = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32) * np.float32(1.4426950408889634 / math.sqrt(dh)))
+    k = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32))
+    v = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32))
+    item = np.repeat(np.arange(len(segs)), segs)
+    q = qs.astype(np.float64) * math.sqrt(dh) * math.log(2.0)        # undo the folded scale for the checker
+    ref = O.attention(q.reshape(n, nh, dh), k.reshape(n, nh, dh).astype(np.float64),
+                      v.reshape(n, nh, dh).astype(np.float64), item[:, None] == item[None, :]).reshape(n, D)
+    qk = dev_bf16(np.concatenate([qs, k], 1))
+    ld = (n + 7) // 8 * 8
+    vt = torch.zeros(D, ld, device=DEV, dtype=torch.bfloat16)
+    vt[:, :n] = dev_bf16(np.ascontiguousarray(v.T))
+    out = torch.zeros(n, D, device=DEV, dtype=torch.bfloat16)
+    B.cs_attention_varlen(qk, vt, out, cu, nh, dh)
+    torch.cuda.synchronize()
+    err = np.abs(out.float().cpu().numpy() - ref).max()
+    print(f"attention dh={dh} segs={segs}: max err {err:.3g}", flush=True)
+    assert err <= 2e-2        # probabilities and outputs are rounded to bf16 (2^-9 relative), |v| up to ~4
+
+
+# ------------------------------------------------------------------ whole encoder task
+def run_encode(w: wl.Workload):
+    enc = B.Encoder(w.cfg, w.weights)
+    out, _ = enc.cs_encode(dev_input(w), w.cu_seqlens, w.grid_thw)
+    torch.cuda.synchronize()
+    return enc, out
+
+
+def test_encode_c1_tiny_and_forward():
+    """One 224x224 image through the tiny fp32 tower; rows land at positions 32..95."""
+    w = wl.c1_tiny()
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, "c1")
+    dst_bits = w.consumer_buffer_bits()
+    dst = torch.from_numpy(dst_bits.view(np.int32)).to(DEV).view(torch.float32)
+    B.cs_forward_embeddings(out, torch.from_numpy(w.placeholder_index).to(DEV), dst)
+    torch.cuda.synchronize()
+    got = dst.view(torch.int32).cpu().numpy().view(np.uint32)
+    src_bits = out.view(torch.int32).cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, O.forward_embeddings(src_bits, w.placeholder_index, dst_bits))
+
+
+@pytest.mark.parametrize("sections", [(0, 20, 20), (8, 16, 16)])
+def test_encode_small_ragged_vit(sections):
+    """7B-shaped layers (hidden 1280, 16x80 heads, MLP 3420, merger 5120->3584) on three small images whose
+    grids are not multiples of the window: truncated edge windows, window and full layers."""
+    w = wl.small_vit(rope_sections=sections)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, f"small_vit{sections}")
+    # bf16 output rows: the same values rounded once more
+    w2 = replace(w, cfg=replace(w.cfg, out_dtype="bf16"))
+    enc2, out2 = run_encode(w2)
+    assert out2.dtype == torch.bfloat16
+    assert torch.equal(out2, out.to(torch.bfloat16))
+    # determinism and batch invariance
+    out3, _ = enc.cs_encode(dev_input(w), w.cu_seqlens, w.grid_thw)
+    torch.cuda.synchronize()
+    assert torch.equal(out3, out)
+    one = w.select_items([1])
+    o1, _ = enc.cs_encode(dev_input(one), one.cu_seqlens, one.grid_thw)
+    torch.cuda.synchronize()
+    a = int(w.out_rows[0])
+    assert (o1 - out[a:a + int(w.out_rows[1])]).abs().max().item() <= 1e-2
+
+
+def test_encode_video_clip_small():
+    cfg = wl.vit_7b_config(2, rope_sections=(8, 16, 16))
+    w = wl.video_workload("small_video", replace(cfg, full_attn_layers=(1,)), 1, 6, (140, 196), seq_len=512)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, "small_video")
+
+
+def test_encode_small_audio():
+    w = wl.audio_workload("small_audio", wl.audio_config(n_layers=2), n_clips=2, n_frames=400, seq_len=256)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, "small_audio")
+
+
+def test_encode_rejects_bad_batches():
+    w = wl.small_vit(n_layers=1, full_layers=())
+    enc = B.Encoder(w.cfg, w.weights)
+    x = dev_input(w)
+    bad_cu = w.cu_seqlens.copy(); bad_cu[1] += 4
+    with pytest.raises(B.CsError) as e:
+        enc.cs_encode(x, bad_cu, w.grid_thw)
+    assert e.value.status == 2
+    odd = w.grid_thw.copy(); odd[0] = (1, 3, 20)
+    with pytest.raises(B.CsError):
+        enc.cs_encode(x, w.cu_seqlens, odd)
+    n_out, ws = enc.cs_encoder_query(w.cu_seqlens, w.grid_thw)
+    out = torch.empty(n_out, w.cfg.out_hidden, device=DEV)
+    small = torch.empty(ws - 256, dtype=torch.uint8, device=DEV)
+    st = B.lib().cs_encode(enc._h, x.data_ptr(), B._i32p(B._i32(w.cu_seqlens)), B._i32p(B._i32(w.grid_thw)),
+                           w.n_items, out.data_ptr(), small.data_ptr(), small.numel(), 0)
+    assert st == 3
+    torch.cuda.synchronize()
