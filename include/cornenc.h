@@ -186,6 +186,26 @@ cs_status cs_linear_bf16(const void* A, int64_t lda, const void* W, const float*
 cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
                               int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream);
 
+/* Timing of one step of the encoder task with HIP events on the caller's stream (measurement
+ * aid; Sec. 2 mentions tracing only in passing).  After cs_encoder_time_step(enc, step), every
+ * cs_encode records an event pair around each launch of that step; cs_encoder_read_timing waits
+ * for the recorded events, returns the summed elapsed milliseconds and the number of launches
+ * since the last read, and clears them.  step = CS_STEP_NONE switches recording off. */
+typedef enum {
+  CS_STEP_NONE = 0,
+  CS_STEP_FRONT = 1,       /* gather/cast, rotary table, patch embed / convolutions */
+  CS_STEP_NORM = 2,        /* RMSNorm / LayerNorm launches inside the blocks        */
+  CS_STEP_QKV = 3,         /* QKV projection with rotary epilogue                   */
+  CS_STEP_ATTN_WINDOW = 4,
+  CS_STEP_ATTN_FULL = 5,
+  CS_STEP_PROJ = 6,        /* attention output projection + residual                */
+  CS_STEP_MLP_UP = 7,      /* gate|up with SwiGLU epilogue (audio: fc1 + GELU)      */
+  CS_STEP_MLP_DOWN = 8,    /* down projection + residual                            */
+  CS_STEP_BACK = 9         /* final norm, merger / pooling, output projection       */
+} cs_step;
+cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
+cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
+
 const char* cs_status_string(cs_status s);
 const char* cs_last_error(void);
 

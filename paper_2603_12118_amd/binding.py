@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libcornenc.so")
 
 CS_F32, CS_BF16 = 0, 1
 CS_ARCH_VIT, CS_ARCH_AUDIO = 0, 1
+STEPS = {"front": 1, "norm": 2, "qkv": 3, "attn_window": 4, "attn_full": 5, "proj": 6, "mlp_up": 7, "mlp_down": 8,
+         "back": 9}
 
 
 class CsError(RuntimeError):
@@ -58,11 +60,13 @@ def lib() -> C.CDLL:
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
         L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
         L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
+        L.cs_encoder_read_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.cs_status_string.argtypes = [C.c_int]
         L.cs_status_string.restype = C.c_char_p
         L.cs_last_error.restype = C.c_char_p
         for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
-                  "cs_linear_bf16", "cs_attention_varlen"):
+                  "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_read_timing"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -144,6 +148,14 @@ class Encoder:
         n_out, ws = C.c_int64(), C.c_size_t()
         _check(lib().cs_encoder_query(self._h, _i32p(cu), _i32p(g), g.shape[0], C.byref(n_out), C.byref(ws)))
         return n_out.value, ws.value
+
+    def cs_encoder_time_step(self, step: int) -> None:
+        _check(lib().cs_encoder_time_step(self._h, step))
+
+    def cs_encoder_read_timing(self):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().cs_encoder_read_timing(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def cs_encode(self, patches, cu_seqlens, grid_thw, out=None, workspace=None, stream=None):
         """patches: device tensor [N, patch_dim] of the config dtype.  Returns (out, workspace)."""

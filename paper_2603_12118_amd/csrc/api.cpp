@@ -87,6 +87,10 @@ struct cs_encoder {
   hipEvent_t stage_ev[2] = {nullptr, nullptr};
   bool stage_used[2] = {false, false};
   int stage_next = 0;
+  // optional per-step event timing
+  int time_step = 0;
+  std::vector<hipEvent_t> ev_pool;   // pairs: start, stop
+  size_t ev_used = 0;
 
   template <class T>
   T* ptr(size_t off) const { return reinterpret_cast<T*>(dev + off); }
@@ -349,6 +353,28 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   return w;
 }
 
+// Records an event pair around the launches of one step when that step is being timed.
+struct StepTimer {
+  cs_encoder* e;
+  hipStream_t stream;
+  bool on;
+  StepTimer(cs_encoder* enc, int step, hipStream_t s) : e(enc), stream(s), on(enc->time_step == step) {
+    if (!on) return;
+    if (e->ev_used + 2 > e->ev_pool.size()) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+      e->ev_pool.push_back(a);
+      e->ev_pool.push_back(b);
+    }
+    (void)hipEventRecord(e->ev_pool[e->ev_used], stream);
+  }
+  ~StepTimer() {
+    if (!on) return;
+    (void)hipEventRecord(e->ev_pool[e->ev_used + 1], stream);
+    e->ev_used += 2;
+  }
+};
+
 static cs_status make_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items, BatchPlan& p) {
   if (e->cfg.arch == CS_ARCH_VIT) return build_vit_plan(e->cfg, cu, grid, n_items, p);
   cs_status st = build_audio_plan(e->cfg, cu, grid, n_items, p);
@@ -425,11 +451,33 @@ cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* we
 void cs_encoder_destroy(cs_encoder* e) {
   if (!e) return;
   if (e->dev) (void)hipFree(e->dev);
+  for (hipEvent_t ev : e->ev_pool) (void)hipEventDestroy(ev);
   for (int s = 0; s < 2; ++s) {
     if (e->stage[s]) (void)hipHostFree(e->stage[s]);
     if (e->stage_ev[s]) (void)hipEventDestroy(e->stage_ev[s]);
   }
   delete e;
+}
+
+cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step) {
+  if (!enc || step < CS_STEP_NONE || step > CS_STEP_BACK) return fail(CS_ERR_INVALID_ARG, "cs_encoder_time_step");
+  enc->time_step = step;
+  return CS_OK;
+}
+
+cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches) {
+  if (!enc || !total_ms || !launches) return fail(CS_ERR_INVALID_ARG, "cs_encoder_read_timing: NULL argument");
+  double sum = 0;
+  for (size_t i = 0; i + 1 < enc->ev_used; i += 2) {
+    CS_HIP(hipEventSynchronize(enc->ev_pool[i + 1]));
+    float ms = 0;
+    CS_HIP(hipEventElapsedTime(&ms, enc->ev_pool[i], enc->ev_pool[i + 1]));
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)(enc->ev_used / 2);
+  enc->ev_used = 0;
+  return CS_OK;
 }
 
 cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw, int32_t n_items,
@@ -517,31 +565,39 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   };
 
   // ---- front end: tokens into the fp32 residual stream x [N, D]
-  if (vit) {
-    if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, c.patch_dim, plan + p.off_src_row, big, e->P_pad, N, stream)) return st;
-    if (e->rope)
-      if (cs_status st = launch_rope_table(plan + p.off_pos, e->ptr<int32_t>(e->axis), e->ptr<float>(e->inv_freq), e->half, rcos, rsin, N, stream)) return st;
-    if (cs_status st = gemm(EPI_F32, big, e->P_pad, e->w_pe, 0, x, D, N, D, e->P_pad, nullptr)) return st;
-  } else {
-    const int64_t R = p.n_pad_rows, C = c.patch_dim;
-    bf16_t* melp = big;
-    bf16_t* c1buf = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(big) + round_up(R * C * 2, 256));
-    if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, (int32_t)C, plan + p.off_mel_src, melp, (int32_t)C, R, stream)) return st;
-    if (cs_status st = launch_zero_rows(c1buf, plan + p.off_zero_rows, p.n_zero_rows, (int32_t)D, stream)) return st;
-    if (cs_status st = gemm(EPI_GELU_BF16, melp, C, e->w_c1, e->b_c1, c1buf, D, R - 2, D, 3 * C, plan + p.off_c1_map)) return st;
-    if (cs_status st = gemm(EPI_GELU_F32, c1buf, 2 * D, e->w_c2, e->b_c2, x, D, R / 2 - 1, D, 3 * D, plan + p.off_c2_map)) return st;
-    if (cs_status st = launch_add_rows(x, e->ptr<float>(e->pe_tab), plan + p.off_pos, N, (int32_t)D, stream)) return st;
+  {
+    StepTimer tm(e, CS_STEP_FRONT, stream);
+    if (vit) {
+      if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, c.patch_dim, plan + p.off_src_row, big, e->P_pad, N, stream)) return st;
+      if (e->rope)
+        if (cs_status st = launch_rope_table(plan + p.off_pos, e->ptr<int32_t>(e->axis), e->ptr<float>(e->inv_freq), e->half, rcos, rsin, N, stream)) return st;
+      if (cs_status st = gemm(EPI_F32, big, e->P_pad, e->w_pe, 0, x, D, N, D, e->P_pad, nullptr)) return st;
+    } else {
+      const int64_t R = p.n_pad_rows, C = c.patch_dim;
+      bf16_t* melp = big;
+      bf16_t* c1buf = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(big) + round_up(R * C * 2, 256));
+      if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, (int32_t)C, plan + p.off_mel_src, melp, (int32_t)C, R, stream)) return st;
+      if (cs_status st = launch_zero_rows(c1buf, plan + p.off_zero_rows, p.n_zero_rows, (int32_t)D, stream)) return st;
+      if (cs_status st = gemm(EPI_GELU_BF16, melp, C, e->w_c1, e->b_c1, c1buf, D, R - 2, D, 3 * C, plan + p.off_c1_map)) return st;
+      if (cs_status st = gemm(EPI_GELU_F32, c1buf, 2 * D, e->w_c2, e->b_c2, x, D, R / 2 - 1, D, 3 * D, plan + p.off_c2_map)) return st;
+      if (cs_status st = launch_add_rows(x, e->ptr<float>(e->pe_tab), plan + p.off_pos, N, (int32_t)D, stream)) return st;
+    }
   }
 
   // ---- transformer blocks
   AttnArgs aa = {};
   aa.qk = qk; aa.vt = vt; aa.ld_vt = w.ld_vt; aa.out = attn; aa.n_tok = (int32_t)N; aa.n_heads = c.n_heads; aa.head_dim = c.head_dim;
   const float q_scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
+  auto norm = [&](size_t gain, size_t bias) {
+    StepTimer tm(e, CS_STEP_NORM, stream);
+    if (vit) return launch_rmsnorm(x, e->ptr<float>(gain), c.norm_eps, xn, N, (int32_t)D, stream);
+    return launch_layernorm(x, e->ptr<float>(gain), e->ptr<float>(bias), c.norm_eps, xn, N, (int32_t)D, stream);
+  };
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& L = e->layers[l];
-    if (vit) { if (cs_status st = launch_rmsnorm(x, e->ptr<float>(L.g1), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
-    else { if (cs_status st = launch_layernorm(x, e->ptr<float>(L.g1), e->ptr<float>(L.be1), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
+    if (cs_status st = norm(L.g1, L.be1)) return st;
     {
+      StepTimer tm(e, CS_STEP_QKV, stream);
       GemmArgs g = {};
       g.A = xn; g.lda = D; g.W = e->ptr<bf16_t>(L.wqkv); g.bias = e->ptr<float>(L.bqkv);
       g.out = qk; g.ldo = 2 * D; g.M = (int32_t)N; g.N = (int32_t)(3 * D); g.K = (int32_t)D;
@@ -550,29 +606,43 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
       if (cs_status st = launch_gemm(EPI_QKV, g, stream)) return st;
     }
     const bool full = !vit || c.window <= 0 || ((c.full_attn_layer_mask >> l) & 1);
-    if (full) {
-      aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256;
-    } else {
-      aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64;
+    {
+      StepTimer tm(e, full ? CS_STEP_ATTN_FULL : CS_STEP_ATTN_WINDOW, stream);
+      if (full) {
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256;
+      } else {
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64;
+      }
+      if (cs_status st = launch_attention(aa, stream)) return st;
     }
-    if (cs_status st = launch_attention(aa, stream)) return st;
-    if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st;
-    if (vit) { if (cs_status st = launch_rmsnorm(x, e->ptr<float>(L.g2), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
-    else { if (cs_status st = launch_layernorm(x, e->ptr<float>(L.g2), e->ptr<float>(L.be2), c.norm_eps, xn, N, (int32_t)D, stream)) return st; }
-    if (vit) { if (cs_status st = gemm(EPI_SWIGLU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, 2 * e->I_pad, D, nullptr)) return st; }
-    else { if (cs_status st = gemm(EPI_GELU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, e->I_pad, D, nullptr)) return st; }
-    if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st;
+    {
+      StepTimer tm(e, CS_STEP_PROJ, stream);
+      if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st;
+    }
+    if (cs_status st = norm(L.g2, L.be2)) return st;
+    {
+      StepTimer tm(e, CS_STEP_MLP_UP, stream);
+      if (vit) { if (cs_status st = gemm(EPI_SWIGLU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, 2 * e->I_pad, D, nullptr)) return st; }
+      else { if (cs_status st = gemm(EPI_GELU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, e->I_pad, D, nullptr)) return st; }
+    }
+    {
+      StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
+      if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st;
+    }
   }
 
   // ---- back end: merged / pooled tokens -> embedding rows
-  if (vit) {
-    const int64_t M = p.n_out, G = (int64_t)c.merge * c.merge * D;
-    if (cs_status st = launch_rmsnorm(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, stream)) return st;
-    if (cs_status st = gemm(EPI_GELU_BF16, xn, G, e->w_m1, e->b_m1, big, e->MH_pad, M, e->MH_pad, G, nullptr)) return st;
-    if (cs_status st = gemm(out_epi, big, e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, e->MH_pad, plan + p.off_out_row)) return st;
-  } else {
-    if (cs_status st = launch_pool_layernorm(x, e->ptr<float>(e->g_p), e->ptr<float>(e->be_p), c.norm_eps, xn, p.n_out, (int32_t)D, c.merge, stream)) return st;
-    if (cs_status st = gemm(out_epi, xn, D, e->w_p, e->b_p, out_embeddings, c.out_hidden, p.n_out, c.out_hidden, D, nullptr)) return st;
+  {
+    StepTimer tm(e, CS_STEP_BACK, stream);
+    if (vit) {
+      const int64_t M = p.n_out, G = (int64_t)c.merge * c.merge * D;
+      if (cs_status st = launch_rmsnorm(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, stream)) return st;
+      if (cs_status st = gemm(EPI_GELU_BF16, xn, G, e->w_m1, e->b_m1, big, e->MH_pad, M, e->MH_pad, G, nullptr)) return st;
+      if (cs_status st = gemm(out_epi, big, e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, e->MH_pad, plan + p.off_out_row)) return st;
+    } else {
+      if (cs_status st = launch_pool_layernorm(x, e->ptr<float>(e->g_p), e->ptr<float>(e->be_p), c.norm_eps, xn, p.n_out, (int32_t)D, c.merge, stream)) return st;
+      if (cs_status st = gemm(out_epi, xn, D, e->w_p, e->b_p, out_embeddings, c.out_hidden, p.n_out, c.out_hidden, D, nullptr)) return st;
+    }
   }
   return CS_OK;
 }
