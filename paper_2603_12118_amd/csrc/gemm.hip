@@ -2,8 +2,9 @@
 //
 // One workgroup owns a BM x BN tile of C and walks K in slices of 64.  Each slice of A and W
 // is staged through LDS in 16-byte chunks whose position inside a 128-byte row is XOR-ed with
-// the row number, so that both the 16-byte stores (8 lanes per row) and the MFMA operand
-// reads (32 rows at one chunk position) spread over all banks.  Waves are laid out WGM x WGN
+// (row / 2) % 8: measured on gfx950, ds_read_b128 serves 16 lanes per pass and the lanes of a pass
+// are not consecutive (rows {0-3,12-15,20-23,24-27} of an operand read share one), and this is the
+// XOR under which both the operand reads and the 16-byte staging stores run at full LDS rate.  Waves are laid out WGM x WGN
 // over the tile; a wave accumulates (BM/WGM) x (BN/WGN) in fp32 with v_mfma_f32_32x32x16_bf16.
 // Global loads for slice k+1 are issued before the MFMAs of slice k and written to the other
 // LDS buffer afterwards, one barrier per slice.
@@ -13,6 +14,7 @@ namespace cs {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
   uint32_t u = __float_as_uint(f);
@@ -26,15 +28,26 @@ __device__ __forceinline__ float lane_xor1(float v) {
   return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
 }
 
+typedef __attribute__((address_space(3))) void lds_void;
+
+// Issues the LDS-direct loads of one 64-wide K slice: every wave instruction moves 64 x 16 bytes
+// from the lanes' global addresses to 1 KB of LDS starting at a wave-uniform address, in lane order.
+template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
+__device__ __forceinline__ void issue_slice(const bf16_t* const* ap, const bf16_t* const* bp,
+                                            int kt, unsigned char* stage, int wave) {
+#pragma unroll
+  for (int i = 0; i < A_LOADS; ++i)
+    __builtin_amdgcn_global_load_lds(ap[i] + kt * 64, (lds_void*)(uintptr_t)(stage + (i * NWAVES + wave) * 1024), 16, 0, 0);
+#pragma unroll
+  for (int i = 0; i < B_LOADS; ++i)
+    __builtin_amdgcn_global_load_lds(bp[i] + kt * 64, (lds_void*)(uintptr_t)(stage + BM * 128 + (i * NWAVES + wave) * 1024), 16, 0, 0);
+}
+
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
-  constexpr int NT = 64 * WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int ROWS_PER_PASS = NT / 8;            // rows covered by one 16-byte load per thread
-  constexpr int A_LOADS = BM / ROWS_PER_PASS, B_LOADS = BN / ROWS_PER_PASS;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
-  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile vs threads");
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -54,29 +67,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   }
   const int m0 = (bid / tiles_n) * BM, n0 = (bid % tiles_n) * BN;
 
-  // ---- global -> LDS staging addresses
-  const int lrow = tid >> 3, lchunk = tid & 7;
-  const uint4* ap[A_LOADS];
-  const uint4* bp[B_LOADS];
-#pragma unroll
-  for (int i = 0; i < A_LOADS; ++i) {
-    int r = m0 + lrow + i * ROWS_PER_PASS;
-    r = r < M ? r : M - 1;
-    ap[i] = reinterpret_cast<const uint4*>(g.A + (int64_t)r * g.lda + lchunk * 8);
-  }
-#pragma unroll
-  for (int i = 0; i < B_LOADS; ++i) {
-    int r = n0 + lrow + i * ROWS_PER_PASS;
-    r = r < N ? r : N - 1;
-    bp[i] = reinterpret_cast<const uint4*>(g.W + (int64_t)r * K + lchunk * 8);
-  }
-  const int st_off = lrow * 128 + ((lchunk ^ (lrow & 7)) << 4);  // same swizzle for every pass (ROWS_PER_PASS % 8 == 0)
-
-  // ---- LDS -> MFMA operand addresses
   const int l31 = lane & 31, lhi = lane >> 5;
   const int a_rd = (wm * WM + l31) * 128;
   const int b_rd = BM * 128 + (wn * WN + l31) * 128;
-  const int sw = lane & 7;
+  const int sw = (l31 >> 1) & 7;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -86,52 +80,68 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[A_LOADS], rb[B_LOADS];
+  // ---- global -> LDS: 16-byte LDS-direct loads.  One wave instruction fills 1 KB of LDS in lane
+  // order (8 rows of 128 bytes), so the XOR swizzle is applied on the global side: the lane that
+  // fills chunk position c' of row r fetches chunk c' ^ ((r/2)%8) of that row.
+  constexpr int NWAVES = WGM * WGN;
+  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
+  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
+  const int lr = lane >> 3;                 // row inside the 8-row group
+  const bf16_t* ap[A_LOADS];
+  const bf16_t* bp[B_LOADS];
 #pragma unroll
-  for (int i = 0; i < A_LOADS; ++i) ra[i] = *ap[i];
+  for (int i = 0; i < A_LOADS; ++i) {
+    const int rt = (i * NWAVES + wave) * 8 + lr;           // row inside the tile
+    int r = m0 + rt;
+    r = r < M ? r : M - 1;
+    ap[i] = g.A + (int64_t)r * g.lda + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
+  }
 #pragma unroll
-  for (int i = 0; i < B_LOADS; ++i) rb[i] = *bp[i];
-#pragma unroll
-  for (int i = 0; i < A_LOADS; ++i) *reinterpret_cast<uint4*>(smem + st_off + i * ROWS_PER_PASS * 128) = ra[i];
-#pragma unroll
-  for (int i = 0; i < B_LOADS; ++i)
-    *reinterpret_cast<uint4*>(smem + BM * 128 + st_off + i * ROWS_PER_PASS * 128) = rb[i];
-  __syncthreads();
-
+  for (int i = 0; i < B_LOADS; ++i) {
+    const int rt = (i * NWAVES + wave) * 8 + lr;
+    int r = n0 + rt;
+    r = r < N ? r : N - 1;
+    bp[i] = g.W + (int64_t)r * K + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
+  }
   const int KT = K >> 6;
+  issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
   for (int kt = 0; kt < KT; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    const bool more = kt + 1 < KT;
-    if (more) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of slice kt has landed
+    __syncthreads();                                     // ... and everyone's; slice kt-1 fully consumed
+    issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, kt + 1 < KT ? kt + 1 : kt, nxt, wave);          // last iteration re-reads slice kt into the idle buffer
+    bf16x8 af[2][TM], bfr[2][TN];
+    {
+      const int coff = ((0 * 2 + lhi) ^ sw) << 4;
 #pragma unroll
-      for (int i = 0; i < A_LOADS; ++i) ra[i] = ap[i][(kt + 1) * 8];
+      for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(cur + a_rd + i * 32 * 128 + coff);
 #pragma unroll
-      for (int i = 0; i < B_LOADS; ++i) rb[i] = bp[i][(kt + 1) * 8];
+      for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(cur + b_rd + j * 32 * 128 + coff);
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const int coff = ((ks * 2 + lhi) ^ sw) << 4;
-      bf16x8 af[TM], bfr[TN];
+      // MFMAs of k-step ks in source order, with one LDS read of k-step ks+1 issued after each of
+      // the first TM+TN of them; scheduling barriers pin this order so that the reads' latency
+      // is covered by the MFMAs that follow.
+      const int coff = (((ks + 1) * 2 + lhi) ^ sw) << 4;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(cur + a_rd + i * 32 * 128 + coff);
+      for (int n = 0; n < TM * TN; ++n) {
+        const int i = n / TN, j = n % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+        if (ks < 3) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(cur + b_rd + j * 32 * 128 + coff);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          for (int q = 2 * n; q < 2 * n + 2 && q < TM + TN; ++q) {   // two reads behind each of the first MFMAs
+            if (q == 0) af[(ks + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(cur + a_rd + coff);
+            else if (q <= TN) bfr[(ks + 1) & 1][q - 1] = *reinterpret_cast<const bf16x8*>(cur + b_rd + (q - 1) * 32 * 128 + coff);
+            else af[(ks + 1) & 1][q - TN] = *reinterpret_cast<const bf16x8*>(cur + a_rd + (q - TN) * 32 * 128 + coff);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < A_LOADS; ++i) *reinterpret_cast<uint4*>(nxt + st_off + i * ROWS_PER_PASS * 128) = ra[i];
-#pragma unroll
-      for (int i = 0; i < B_LOADS; ++i)
-        *reinterpret_cast<uint4*>(nxt + BM * 128 + st_off + i * ROWS_PER_PASS * 128) = rb[i];
-    }
-    __syncthreads();
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the redundant last prefetch must land before LDS is released
 
   // ---- epilogue.  Accumulator register r of lane l in a 32x32 tile is the element
   //      (row 8*(r/4) + 4*(l/32) + r%4, column l%32).
