@@ -2,8 +2,8 @@
 //
 // One workgroup owns a BM x BN tile of C and walks K in slices of 64.  Each slice of A and W is
 // brought into LDS with 16-byte LDS-direct loads (no staging registers, no LDS store
-// instructions), double-buffered: the loads of slice k+1 are issued right after the barrier that
-// publishes slice k and have the whole MFMA phase of slice k to land.
+// instructions), double-buffered: the loads of slice k+1 are issued one by one between the MFMAs
+// of the first half of slice k and have the rest of that slice to land.
 //
 // LDS layout: rows of 128 bytes (64 bf16), the 16-byte chunk at position c of row r holds chunk
 // c ^ ((r/2) % 8) of that row.  Measured on gfx950, ds_read_b128 serves 16 lanes per pass and the
@@ -56,6 +56,17 @@ __device__ __forceinline__ void issue_slice(const bf16_t* const* ap, const bf16_
     __builtin_amdgcn_global_load_lds(bp[i] + kt * 64, (lds_void*)(uintptr_t)(stage + BM * 128 + (i * NWAVES + wave) * 1024), 16, 0, 0);
 }
 
+// One of the A_LOADS + B_LOADS loads of a slice, by index.
+template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
+__device__ __forceinline__ void issue_one(const bf16_t* const* ap, const bf16_t* const* bp, int l, int kt,
+                                          unsigned char* stage, int wave) {
+  if (l < A_LOADS)
+    __builtin_amdgcn_global_load_lds(ap[l] + kt * 64, (lds_void*)(uintptr_t)(stage + (l * NWAVES + wave) * 1024), 16, 0, 0);
+  else
+    __builtin_amdgcn_global_load_lds(bp[l - A_LOADS] + kt * 64,
+                                     (lds_void*)(uintptr_t)(stage + BM * 128 + ((l - A_LOADS) * NWAVES + wave) * 1024), 16, 0, 0);
+}
+
 // The K loop.  W_FIRST: accumulate C^T blocks (lane = row m, registers = columns n); otherwise
 // C blocks (lane = column n, registers = rows m).
 template <int BM, int BN, int WGM, int WGN, bool W_FIRST>
@@ -67,6 +78,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   constexpr int NWAVES = WGM * WGN;
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
+  constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N, K = g.K;
@@ -106,8 +118,11 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's part of slice kt has landed
     __syncthreads();                                    // ... and everyone's; slice kt-1 fully consumed
-    // the last iteration re-reads slice kt into the idle buffer: no branch around the loads
-    issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, kt + 1 < KT ? kt + 1 : kt, nxt, wave);
+    // The loads of slice kt+1 go out one at a time between the MFMAs of the first k-steps: issued
+    // in one burst behind the barrier they queue in the texture-address unit (16 clocks each, all
+    // waves at once) and every wave sits in the issue stall instead of feeding the MFMA pipe.
+    // The last iteration re-reads slice kt into the idle buffer: no branch around the loads.
+    const int kn = kt + 1 < KT ? kt + 1 : kt;
     bf16x8 af[2][TM], bfr[2][TN];
     {
       const int coff = (lhi ^ sw) << 4;
@@ -129,6 +144,12 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
         else
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+        if (ks < SPREAD_KS) {
+          constexpr int LT = A_LOADS + B_LOADS, SLOTS = SPREAD_KS * TM * TN;
+#pragma unroll
+          for (int l = 0; l < LT; ++l)
+            if (l * SLOTS / LT == ks * TM * TN + n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
+        }
         if (ks < 3) {
 #pragma unroll
           for (int q = 2 * n; q < 2 * n + 2 && q < TM + TN; ++q) {
@@ -286,7 +307,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 template <int BM, int BN, int WGM, int WGN, int EPI>
 static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = 2 * (BM + BN) * 128;
+    constexpr int LDS = 2 * (BM + BN) * 128;
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI>;
   static bool attr_set = false;  // one attribute call per instantiation
   if (!attr_set) {
@@ -301,10 +322,16 @@ static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
 
 template <int EPI>
 static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
-  // Tile choice: 256x256 when that still gives every CU work, else 128x128.
-  const int64_t big = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  // Tile choice by the number of workgroups it yields for the 256 CUs.
+  const int64_t tm = (g.M + 255) / 256;
+  const int64_t big = tm * ((g.N + 255) / 256);
   const bool big_ok = EPI != EPI_QKV || (2 * g.hidden) % 256 == 0;
   if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+  if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
+    // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
+    // workgroups, one round of the chip at M = 8192
+    if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+  }
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }
 
