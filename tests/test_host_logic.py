@@ -1,0 +1,121 @@
+"""CPU-only tests of the library's host side: the shared object loads and exports every entry point the
+header declares, and the batch planner (internal token order, windows, output rows, validation) agrees
+with brute-force enumeration written here.  No compute call is made (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import encoder_oracle as O
+from paper_2603_12118_amd import binding as B
+from paper_2603_12118_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "cornenc.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(cs_[a-z_0-9]+)\s*\(", hdr))
+    assert {"cs_encoder_create", "cs_encode", "cs_forward_embeddings", "cs_encoder_query", "cs_encoder_destroy",
+            "cs_plan_tokens", "cs_linear_bf16", "cs_attention_varlen", "cs_status_string", "cs_last_error",
+            "cs_encoder_time_step", "cs_encoder_read_timing"} <= names
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
+    assert B.lib().cs_status_string(0) == b"ok"
+    assert C.sizeof(B.cs_encoder_config) == 88
+
+
+def brute_plan(grid, window, merge=2):
+    """Internal order by definition: item, frame, window (row-major), 2x2 group (row-major), patch."""
+    src, out_row, win_cu = [], [], [0]
+    base = obase = 0
+    for (T, h, w) in grid:
+        for t in range(T):
+            for r0 in range(0, h, window):
+                for c0 in range(0, w, window):
+                    for R in range(r0, min(r0 + window, h), merge):
+                        for Cc in range(c0, min(c0 + window, w), merge):
+                            out_row.append(obase + (t * (h // merge) + R // merge) * (w // merge) + Cc // merge)
+                            for dr in range(merge):
+                                for dc in range(merge):
+                                    src.append(base + (t * h + R + dr) * w + Cc + dc)
+                    win_cu.append(len(src))
+        base += T * h * w
+        obase += T * (h // merge) * (w // merge)
+    return np.array(src), np.array(out_row), np.array(win_cu)
+
+
+@pytest.mark.parametrize("grid", [[(1, 4, 4)], [(1, 6, 10)], [(1, 18, 34)], [(3, 10, 12)], [(1, 32, 32)] * 2,
+                                  [(1, 84, 36), (1, 24, 40), (2, 2, 2)]])
+def test_plan_matches_brute_force_and_checker_geometry(grid):
+    cfg = wl.vit_7b_config()
+    g = np.array(grid, np.int32)
+    cu = np.concatenate([[0], np.cumsum(g.prod(1))]).astype(np.int32)
+    src, out_row, win_cu = B.cs_plan_tokens(cfg, cu, g)
+    bs, bo, bw = brute_plan(grid, 8)
+    assert np.array_equal(src, bs) and np.array_equal(out_row, bo) and np.array_equal(win_cu, bw)
+    n = int(cu[-1])
+    assert sorted(src.tolist()) == list(range(n))                      # a permutation
+    assert sorted(out_row.tolist()) == list(range(n // 4))
+    # windows of the plan are exactly the checker's attention classes
+    item, pos = O.token_coords(g)
+    allowed = O.attention_allowed(item, pos, 8)
+    for a, b in zip(win_cu[:-1], win_cu[1:]):
+        members = np.sort(src[a:b])
+        assert np.array_equal(np.flatnonzero(allowed[members[0]]), members)
+    # four consecutive internal tokens feed one merged token, in the checker's concat order
+    mi = O.merge_index(g, 2)
+    assert np.array_equal(src.reshape(-1, 4), mi[out_row])
+
+
+def test_plan_full_attention_config_keeps_merge_groups():
+    cfg = wl.vit_tiny_config()
+    src, out_row, win_cu = B.cs_plan_tokens(cfg, [0, 256], [[1, 16, 16]])
+    assert len(win_cu) == 1                                            # no windows
+    assert np.array_equal(src.reshape(-1, 4), O.merge_index(np.array([[1, 16, 16]]), 2)[out_row])
+
+
+@pytest.mark.parametrize("cu,grid,status", [
+    ([0, 17], [[1, 4, 4]], 2),            # token count does not match the grid
+    ([1, 17], [[1, 4, 4]], 2),            # does not start at 0
+    ([0, 15], [[1, 3, 5]], 2),            # odd grid
+    ([0, 0], [[0, 4, 4]], 2),             # empty item
+])
+def test_plan_rejects_inconsistent_batches(cu, grid, status):
+    with pytest.raises(B.CsError) as e:
+        B.cs_plan_tokens(wl.vit_7b_config(), cu, grid)
+    assert e.value.status == status and B.last_error()
+
+
+def test_config_validation_on_host():
+    from dataclasses import replace
+    bad = replace(wl.vit_7b_config(), head_dim=72, n_heads=16, hidden=1152)
+    with pytest.raises(B.CsError) as e:
+        B.cs_plan_tokens(bad, [0, 16], [[1, 4, 4]])
+    assert e.value.status == 5
+    bad = replace(wl.vit_7b_config(), rope_sections=(0, 20, 19))
+    with pytest.raises(B.CsError):
+        B.cs_plan_tokens(bad, [0, 16], [[1, 4, 4]])
+
+
+def test_forward_embeddings_argument_errors_need_no_gpu():
+    assert B.cs_forward_embeddings_raw(16, 16, 16, -1, 4, 8, B.CS_BF16) == 1       # negative size
+    assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 7, B.CS_BF16) == 5        # 14-byte rows
+    assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 8, 9) == 1                # bad dtype
+    assert B.cs_forward_embeddings_raw(8, 16, 16, 4, 4, 8, B.CS_BF16) == 1         # misaligned src
+    assert B.cs_forward_embeddings_raw(0, 0, 0, 0, 4, 8, B.CS_BF16) == 0           # empty: no-op
+
+
+def test_flop_model_matches_hand_count():
+    import bench
+    f = bench.algorithmic_flops(wl.vit_7b_config(), np.array([[1, 32, 32]] * 8))
+    n, d, i = 8192, 1280, 3420
+    lin = 2 * n * 1176 * d + 32 * (2 * n * d * 3 * d + 2 * n * d * d + 3 * 2 * n * d * i) + \
+        2 * 2048 * 5120 * 5120 + 2 * 2048 * 5120 * 3584
+    att = 28 * 4 * (8 * 16 * 64 ** 2) * d + 4 * 4 * (8 * 1024 ** 2) * d
+    assert f["total"] == lin + att
+    assert abs(f["total"] / 1e12 - 10.78) < 0.01
