@@ -45,6 +45,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
   const bf16_t* kbase = a.qk + hidden + head * DH;
   const bf16_t* vbase = a.vt + (int64_t)head * DH * a.ld_vt;
   const int last_tok = a.n_tok - 1;
+  const int vt_last = ((a.n_tok + 3) & ~3) - 4;   // last 4-token chunk of a V^T row that was written
 
   // ---- this wave's queries as B operands: lane = query column, 8 consecutive dims per k-step
   const int qw = w.q0 + wave * 64;
@@ -67,24 +68,54 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
       for (int r = 0; r < 16; ++r) o[it][dt][r] = 0.f;
   float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
 
-  for (int kv = w.kv0; kv < w.kv1; kv += 64) {
-    __syncthreads();  // previous tile fully consumed
-    // ---- stage K tile [64 keys][DH] and V^T tile [DH][64 keys]
-    for (int c = tid; c < 64 * KCH; c += NT) {
+  // ---- K / V^T tile staging: global -> registers (all loads of a tile in flight together, issued
+  // before the MFMAs of the previous tile) -> LDS.
+  constexpr int K_PT = (64 * KCH + NT - 1) / NT;   // 16-byte chunks of the K tile per thread
+  constexpr int V_PT = (DH * 16 + NT - 1) / NT;    // 8-byte chunks of the V^T tile per thread
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  u32x4 kreg[K_PT];
+  u32x2 vreg[V_PT];
+  auto load_tile = [&](int kv) {
+#pragma unroll
+    for (int u = 0; u < K_PT; ++u) {
+      int c = tid + u * NT;
+      c = c < 64 * KCH ? c : 64 * KCH - 1;
       const int r = c / KCH, ch = c % KCH;
       int row = kv + r;
       row = row < last_tok ? row : last_tok;
-      const uint4 val = *reinterpret_cast<const uint4*>(kbase + (int64_t)row * ldq + ch * 8);
-      *reinterpret_cast<uint4*>(k_lds + r * KSTR + ch * 16) = val;
+      kreg[u] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)row * ldq + ch * 8);
     }
-    for (int c = tid; c < DH * 16; c += NT) {
+#pragma unroll
+    for (int u = 0; u < V_PT; ++u) {
+      int c = tid + u * NT;
+      c = c < DH * 16 ? c : DH * 16 - 1;
       const int d = c >> 4, ch = c & 15;
       int tok = kv + ch * 4;
-      tok = tok < a.n_tok - 4 ? tok : a.n_tok - 4;   // n_tok is a multiple of 4
-      const uint2 val = *reinterpret_cast<const uint2*>(vbase + (int64_t)d * a.ld_vt + tok);
-      *reinterpret_cast<uint2*>(v_lds + d * VSTR + ch * 8) = val;
+      tok = tok < vt_last ? tok : vt_last;
+      vreg[u] = *reinterpret_cast<const u32x2*>(vbase + (int64_t)d * a.ld_vt + tok);
     }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int u = 0; u < K_PT; ++u) {
+      const int c = tid + u * NT;
+      if (c < 64 * KCH) *reinterpret_cast<u32x4*>(k_lds + (c / KCH) * KSTR + (c % KCH) * 16) = kreg[u];
+    }
+#pragma unroll
+    for (int u = 0; u < V_PT; ++u) {
+      const int c = tid + u * NT;
+      if (c < DH * 16) *reinterpret_cast<u32x2*>(v_lds + (c >> 4) * VSTR + (c & 15) * 8) = vreg[u];
+    }
+  };
+
+  load_tile(w.kv0);
+  for (int kv = w.kv0; kv < w.kv1; kv += 64) {
+    __syncthreads();  // previous tile fully consumed
+    store_tile();
     __syncthreads();
+    if (kv + 64 < w.kv1) load_tile(kv + 64);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
     f32x16 s[2][2];
@@ -195,7 +226,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
 
 cs_status launch_attention(const AttnArgs& a, hipStream_t stream) {
   if (a.n_work <= 0) return CS_OK;
-  if (a.n_tok < 4 || (a.n_tok & 3)) return fail(CS_ERR_UNSUPPORTED, "attention: token count must be a multiple of 4");
+  if (a.n_tok < 4 || a.ld_vt < ((a.n_tok + 3) & ~3)) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt too small");
   if (a.ld_vt & 3) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt must be a multiple of 4");
   dim3 grid(a.n_work, a.n_heads);
   if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 1>), grid, dim3(64), 0, stream, a);

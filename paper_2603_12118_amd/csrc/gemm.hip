@@ -78,6 +78,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   constexpr int NWAVES = WGM * WGN;
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
+  constexpr int RD_PER = 2;  // LDS reads of the next k-step issued behind each of the first MFMAs
   constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -152,7 +153,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
         }
         if (ks < 3) {
 #pragma unroll
-          for (int q = 2 * n; q < 2 * n + 2 && q < TM + TN; ++q) {
+          for (int q = RD_PER * n; q < RD_PER * n + RD_PER && q < TM + TN; ++q) {
             if (q == 0) af[(ks + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(cur + a_rd + coff);
             else if (q <= TN) bfr[(ks + 1) & 1][q - 1] = *reinterpret_cast<const bf16x8*>(cur + b_rd + (q - 1) * 32 * 128 + coff);
             else af[(ks + 1) & 1][q - TN] = *reinterpret_cast<const bf16x8*>(cur + a_rd + (q - TN) * 32 * 128 + coff);
