@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the path separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference reading for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; the encoder task shards by item across replicas "
@@ -90,6 +92,13 @@ def main() -> int:
         enc.cs_encode(x, w.cu_seqlens, w.grid_thw, out=out, workspace=workspace)
         B.cs_forward_embeddings(out, idx, dst)
 
+    if args.calibration_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
