@@ -18,10 +18,12 @@ namespace cs {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ uint32_t f2bf_a(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+typedef float f32x2_a __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_a __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even)
+__device__ __forceinline__ uint32_t pack2_a(float a, float b) {
+  const f32x2_a v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_a));
 }
 
 template <int DH, int NW>
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
             const float p0 = exp2f(s[it][jt][8 * u + 2 * e] - mnew);
             const float p1 = exp2f(s[it][jt][8 * u + 2 * e + 1] - mnew);
             sum += p0 + p1;
-            pk[e] = f2bf_a(p0) | (f2bf_a(p1) << 16);
+            pk[e] = pack2_a(p0, p1);
           }
           uint4 t = make_uint4(pk[0], pk[1], pk[2], pk[3]);
           pf[it][jt * 2 + u] = *reinterpret_cast<bf16x8*>(&t);
@@ -216,8 +218,8 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
         const int d = dt * 32 + 8 * g + 4 * lhi;
         if (d < DH) {
           uint2 pk;
-          pk.x = f2bf_a(o[it][dt][4 * g + 0] * inv) | (f2bf_a(o[it][dt][4 * g + 1] * inv) << 16);
-          pk.y = f2bf_a(o[it][dt][4 * g + 2] * inv) | (f2bf_a(o[it][dt][4 * g + 3] * inv) << 16);
+          pk.x = pack2_a(o[it][dt][4 * g + 0] * inv, o[it][dt][4 * g + 1] * inv);
+          pk.y = pack2_a(o[it][dt][4 * g + 2] * inv, o[it][dt][4 * g + 3] * inv);
           *reinterpret_cast<uint2*>(orow + d) = pk;
         }
       }

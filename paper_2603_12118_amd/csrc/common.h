@@ -32,7 +32,8 @@ enum GemmEpilogue {
   EPI_GELU_F32 = 3,   // gelu(acc + bias) -> fp32
   EPI_RESADD_F32 = 4, // out += acc + bias   (fp32 residual stream)
   EPI_SWIGLU_BF16 = 5,// weight rows interleaved in blocks of 32: gate | up; out[:, j] = silu(g) * u
-  EPI_QKV = 6         // q,k: bias, rotary, (q: scale) -> bf16 row-major; v: bias -> bf16 transposed
+  EPI_QKV = 6,        // q,k: bias, rotary, (q: scale) -> bf16 row-major; v: bias -> bf16 transposed
+  EPI_GELU_SPLIT = 7  // v = gelu(acc + bias) -> bf16 hi at column n and bf16 lo = v - hi at column N + n
 };
 
 struct GemmArgs {
@@ -47,8 +48,7 @@ struct GemmArgs {
   // EPI_QKV only
   bf16_t* vt;        // [hidden, ld_vt]
   int64_t ld_vt;
-  const float* rope_cos;   // [M, head_dim/2] or nullptr (no rotary)
-  const float* rope_sin;
+  const float* rope_cs;    // [M, head_dim/2, 2] = (cos, sin) per rotary pair, or nullptr (no rotary)
   int32_t hidden;    // q columns [0,hidden), k [hidden,2 hidden), v [2 hidden, 3 hidden)
   int32_t head_dim;
   float q_scale;
@@ -74,6 +74,9 @@ cs_status launch_attention(const AttnArgs& a, hipStream_t stream);
 // ---- row-wise and copy kernels ----------------------------------------------------------
 cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
                          hipStream_t s);
+// y[g, 0:group*dim) = bf16 hi parts of `group` consecutive normalised rows, y[g, group*dim : 2*group*dim) = lo parts
+cs_status launch_rmsnorm_split(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                               int32_t group, hipStream_t s);
 cs_status launch_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
                            int64_t rows, int32_t dim, hipStream_t s);
 // y[r] = layernorm(mean of `pool` consecutive rows of x)
@@ -82,9 +85,9 @@ cs_status launch_pool_layernorm(const float* x, const float* gain, const float* 
 // dst[r, 0:dst_cols) = bf16(src[src_row[r], 0:src_cols)) padded with zeros; src_row < 0 gives a zero row
 cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols, const int32_t* src_row,
                              bf16_t* dst, int32_t dst_cols, int64_t rows, hipStream_t s);
-// cos/sin[n, j] of pos[n, axis[j]] * inv_freq[j]
+// out[n, j] = (cos, sin) of pos[n, axis[j]] * inv_freq[j]
 cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half,
-                            float* cos_out, float* sin_out, int64_t n_tok, hipStream_t s);
+                            float* cos_sin_out, int64_t n_tok, hipStream_t s);
 // x[r, :] += table[pos[r], :]
 cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim,
                           hipStream_t s);

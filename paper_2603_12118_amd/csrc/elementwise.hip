@@ -4,10 +4,12 @@
 
 namespace cs {
 
-__device__ __forceinline__ uint32_t f2bf_e(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+typedef float f32x2_e __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_e __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even)
+__device__ __forceinline__ uint32_t pack2_e(float a, float b) {
+  const f32x2_e v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_e));
 }
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -21,7 +23,7 @@ constexpr int NORM_MAX_V4 = 8;  // a wave keeps a row of up to 64*4*8 = 2048 flo
 template <int MODE>
 __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                    const float* __restrict__ bias, float eps,
-                                                   bf16_t* __restrict__ y, int64_t rows, int dim, int pool) {
+                                                   bf16_t* __restrict__ y, int64_t rows, int dim, int pool, int split_group) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -68,9 +70,19 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
       const float o0 = (v[i].x - mean) * rstd * g.x + b.x, o1 = (v[i].y - mean) * rstd * g.y + b.y;
       const float o2 = (v[i].z - mean) * rstd * g.z + b.z, o3 = (v[i].w - mean) * rstd * g.w + b.w;
       uint2 pk;
-      pk.x = f2bf_e(o0) | (f2bf_e(o1) << 16);
-      pk.y = f2bf_e(o2) | (f2bf_e(o3) << 16);
-      reinterpret_cast<uint2*>(y + row * dim)[c] = pk;
+      pk.x = pack2_e(o0, o1);
+      pk.y = pack2_e(o2, o3);
+      if (split_group == 0) {
+        reinterpret_cast<uint2*>(y + row * dim)[c] = pk;
+      } else {
+        // hi | lo halves of a row of `split_group` tokens: lo = value - hi, again rounded to bf16
+        bf16_t* dst = y + (row / split_group) * (2 * split_group * dim) + (row % split_group) * dim;
+        reinterpret_cast<uint2*>(dst)[c] = pk;
+        uint2 lo;
+        lo.x = pack2_e(o0 - __uint_as_float(pk.x << 16), o1 - __uint_as_float(pk.x & 0xFFFF0000u));
+        lo.y = pack2_e(o2 - __uint_as_float(pk.y << 16), o3 - __uint_as_float(pk.y & 0xFFFF0000u));
+        reinterpret_cast<uint2*>(dst + split_group * dim)[c] = lo;
+      }
     }
   }
 }
@@ -87,7 +99,18 @@ cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
-                     rows, dim, 1);
+                     rows, dim, 1, 0);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+cs_status launch_rmsnorm_split(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                               int32_t group, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (cs_status st = norm_check(rows, dim)) return st;
+  if (group < 1 || rows % group) return fail(CS_ERR_INVALID_ARG, "rmsnorm_split: rows must be a multiple of the group");
+  hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
+                     rows, dim, 1, group);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -97,7 +120,7 @@ cs_status launch_layernorm(const float* x, const float* gain, const float* bias,
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y, rows,
-                     dim, 1);
+                     dim, 1, 0);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -108,7 +131,7 @@ cs_status launch_pool_layernorm(const float* x, const float* gain, const float* 
   if (cs_status st = norm_check(out_rows, dim)) return st;
   if (pool < 1) return fail(CS_ERR_INVALID_ARG, "pool_layernorm: pool < 1");
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y,
-                     out_rows, dim, pool);
+                     out_rows, dim, pool, 0);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -130,8 +153,8 @@ __global__ __launch_bounds__(256) void gather_cast_kernel(const void* __restrict
         pk = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(src) + sr * src_cols + c);
       } else {
         const float4 v = *reinterpret_cast<const float4*>(static_cast<const float*>(src) + sr * src_cols + c);
-        pk.x = f2bf_e(v.x) | (f2bf_e(v.y) << 16);
-        pk.y = f2bf_e(v.z) | (f2bf_e(v.w) << 16);
+        pk.x = pack2_e(v.x, v.y);
+        pk.y = pack2_e(v.z, v.w);
       }
     }
     *reinterpret_cast<uint2*>(dst + r * dst_cols + c) = pk;
@@ -153,11 +176,10 @@ cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols,
   return CS_OK;
 }
 
-// ---- rotary cos/sin table
+// ---- rotary table: (cos, sin) interleaved per pair, so the QKV epilogue fetches two pairs in 16 bytes
 __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos, const int32_t* __restrict__ axis,
                                                          const float* __restrict__ inv_freq, int half,
-                                                         float* __restrict__ cos_out, float* __restrict__ sin_out,
-                                                         int64_t total) {
+                                                         float2* __restrict__ out, int64_t total) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= total) return;
   const int64_t n = t / half;
@@ -165,16 +187,15 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
   const float ang = (float)pos[n * 3 + axis[j]] * inv_freq[j];
   float sn, cs_;
   sincosf(ang, &sn, &cs_);
-  cos_out[t] = cs_;
-  sin_out[t] = sn;
+  out[t] = make_float2(cs_, sn);
 }
 
-cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half, float* cos_out,
-                            float* sin_out, int64_t n_tok, hipStream_t s) {
+cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half, float* cos_sin_out,
+                            int64_t n_tok, hipStream_t s) {
   const int64_t total = n_tok * half;
   if (total <= 0) return CS_OK;
   hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pos, axis, inv_freq, half,
-                     cos_out, sin_out, total);
+                     reinterpret_cast<float2*>(cos_sin_out), total);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }

@@ -29,16 +29,12 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void lds_void;
 
-__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+// four floats -> four bf16 (v_cvt_pk_bf16_f32, round to nearest even), as 8 bytes
 __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
-  u32x2 r;
-  r.x = f2bf(a) | (f2bf(b) << 16);
-  r.y = f2bf(c) | (f2bf(d) << 16);
-  return r;
+  const f32x4 v = {a, b, c, d};
+  const bf16x4 h = __builtin_convertvector(v, bf16x4);
+  return __builtin_bit_cast(u32x2, h);
 }
 __device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
@@ -272,12 +268,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
           if (g.bias) b = *reinterpret_cast<const f32x4*>(g.bias + n);
           float v0 = acc[i][j][4 * q] + b[0], v1 = acc[i][j][4 * q + 1] + b[1];
           float v2 = acc[i][j][4 * q + 2] + b[2], v3 = acc[i][j][4 * q + 3] + b[3];
-          if (g.rope_cos) {
-            const int p = ((n % g.hidden) % g.head_dim) >> 1;
-            const f32x2 c = *reinterpret_cast<const f32x2*>(g.rope_cos + (int64_t)m * half + p);
-            const f32x2 s = *reinterpret_cast<const f32x2*>(g.rope_sin + (int64_t)m * half + p);
-            const float r0 = v0 * c.x - v1 * s.x, r1 = v1 * c.x + v0 * s.x;
-            const float r2 = v2 * c.y - v3 * s.y, r3 = v3 * c.y + v2 * s.y;
+          if (g.rope_cs) {
+            const int p = ((n % g.hidden) % g.head_dim) >> 1;   // first of the two rotary pairs held here
+            const f32x4 cs = *reinterpret_cast<const f32x4*>(g.rope_cs + ((int64_t)m * half + p) * 2);  // cos,sin,cos,sin
+            const float r0 = v0 * cs[0] - v1 * cs[1], r1 = v1 * cs[0] + v0 * cs[1];
+            const float r2 = v2 * cs[2] - v3 * cs[3], r3 = v3 * cs[2] + v2 * cs[3];
             v0 = r0; v1 = r1; v2 = r2; v3 = r3;
           }
           const float sc = n < g.hidden ? g.q_scale : 1.0f;
@@ -294,11 +289,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
           if (g.bias) v += *reinterpret_cast<const f32x4*>(g.bias + n);
-          if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32) {
+          if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
           }
-          if constexpr (EPI == EPI_BF16 || EPI == EPI_GELU_BF16) {
+          if constexpr (EPI == EPI_GELU_SPLIT) {
+            bf16_t* o = static_cast<bf16_t*>(g.out) + row * g.ldo + n;
+            const u32x2 hi = pack4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<u32x2*>(o) = hi;
+            *reinterpret_cast<u32x2*>(o + N) = pack4(v[0] - __uint_as_float(hi.x << 16), v[1] - __uint_as_float(hi.x & 0xFFFF0000u),
+                                                     v[2] - __uint_as_float(hi.y << 16), v[3] - __uint_as_float(hi.y & 0xFFFF0000u));
+          } else if constexpr (EPI == EPI_BF16 || EPI == EPI_GELU_BF16) {
             *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.out) + row * g.ldo + n) = pack4(v[0], v[1], v[2], v[3]);
           } else if constexpr (EPI == EPI_RESADD_F32) {
             f32x4* p = reinterpret_cast<f32x4*>(static_cast<float*>(g.out) + row * g.ldo + n);
@@ -355,6 +356,7 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream) {
     case EPI_F32: return launch_epi<EPI_F32>(g, stream);
     case EPI_GELU_BF16: return launch_epi<EPI_GELU_BF16>(g, stream);
     case EPI_GELU_F32: return launch_epi<EPI_GELU_F32>(g, stream);
+    case EPI_GELU_SPLIT: return launch_epi<EPI_GELU_SPLIT>(g, stream);
     case EPI_RESADD_F32: return launch_epi<EPI_RESADD_F32>(g, stream);
     case EPI_SWIGLU_BF16:
       if (g.N & 63) return fail(CS_ERR_UNSUPPORTED, "gemm: swiglu needs N % 64 == 0");
