@@ -26,7 +26,7 @@ __device__ __forceinline__ uint32_t pack2_a(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_a));
 }
 
-template <int DH, int NW>
+template <int DH, int NW, int QT>
 __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int KS = DH / 16;            // k-steps of the score product
@@ -50,10 +50,10 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
   const int vt_last = ((a.n_tok + 3) & ~3) - 4;   // last 4-token chunk of a V^T row that was written
 
   // ---- this wave's queries as B operands: lane = query column, 8 consecutive dims per k-step
-  const int qw = w.q0 + wave * 64;
-  bf16x8 qf[2][KS];
+  const int qw = w.q0 + wave * (32 * QT);
+  bf16x8 qf[QT][KS];
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < QT; ++it) {
     int row = qw + it * 32 + l31;
     row = row < last_tok ? row : last_tok;
 #pragma unroll
@@ -61,14 +61,19 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
       qf[it][ks] = *reinterpret_cast<const bf16x8*>(qbase + (int64_t)row * ldq + ks * 16 + lhi * 8);
   }
 
-  f32x16 o[2][DT];
+  f32x16 o[QT][DT];
 #pragma unroll
-  for (int it = 0; it < 2; ++it)
+  for (int it = 0; it < QT; ++it)
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[it][dt][r] = 0.f;
-  float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
+  float mrun[QT], lrun[QT];
+#pragma unroll
+  for (int it = 0; it < QT; ++it) {
+    mrun[it] = -INFINITY;
+    lrun[it] = 0.f;
+  }
 
   // ---- K / V^T tile staging: global -> registers (all loads of a tile in flight together, issued
   // before the MFMAs of the previous tile) -> LDS.
@@ -120,9 +125,9 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
-    f32x16 s[2][2];
+    f32x16 s[QT][2];
 #pragma unroll
-    for (int it = 0; it < 2; ++it)
+    for (int it = 0; it < QT; ++it)
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
       for (int jt = 0; jt < 2; ++jt) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + (jt * 32 + l31) * KSTR + ks * 32 + lhi * 16);
 #pragma unroll
-        for (int it = 0; it < 2; ++it)
+        for (int it = 0; it < QT; ++it)
           s[it][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[it][ks], s[it][jt], 0, 0, 0);
       }
     }
@@ -145,15 +150,15 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
         for (int r = 0; r < 16; ++r) {
           const int key = kv + jt * 32 + 8 * (r >> 2) + 4 * lhi + (r & 3);
           if (key >= w.kv1) {
-            s[0][jt][r] = -INFINITY;
-            s[1][jt][r] = -INFINITY;
+#pragma unroll
+            for (int it = 0; it < QT; ++it) s[it][jt][r] = -INFINITY;
           }
         }
     }
     // ---- online softmax, per query column
-    bf16x8 pf[2][4];
+    bf16x8 pf[QT][4];
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
+    for (int it = 0; it < QT; ++it) {
       float mx = s[it][0][0];
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt)
@@ -197,7 +202,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
         t.x = lo.x; t.y = lo.y; t.z = hi.x; t.w = hi.y;
         const bf16x8 vf = *reinterpret_cast<bf16x8*>(&t);
 #pragma unroll
-        for (int it = 0; it < 2; ++it)
+        for (int it = 0; it < QT; ++it)
           o[it][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[it][ku], o[it][dt], 0, 0, 0);
       }
     }
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
 
   // ---- normalise and store: register r of o[it][dt] is dim dt*32 + 8*(r/4) + 4*lhi + r%4 of query it*32 + lane%32
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
+  for (int it = 0; it < QT; ++it) {
     const float l = lrun[it] + __shfl_xor(lrun[it], 32);
     const float inv = 1.0f / l;
     const int q = qw + it * 32 + l31;
@@ -231,10 +236,11 @@ cs_status launch_attention(const AttnArgs& a, hipStream_t stream) {
   if (a.n_tok < 4 || a.ld_vt < ((a.n_tok + 3) & ~3)) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt too small");
   if (a.ld_vt & 3) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt must be a multiple of 4");
   dim3 grid(a.n_work, a.n_heads);
-  if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 1>), grid, dim3(64), 0, stream, a);
-  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 4>), grid, dim3(256), 0, stream, a);
-  else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 1>), grid, dim3(64), 0, stream, a);
-  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 4>), grid, dim3(256), 0, stream, a);
+  // 64-query work items (window layers): two waves of 32 queries; 256-query items: four waves of 64
+  if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 2, 1>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 4, 2>), grid, dim3(256), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 2, 1>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 4, 2>), grid, dim3(256), 0, stream, a);
   else return fail(CS_ERR_UNSUPPORTED, "attention: head_dim must be 64 or 80 and q_per_block 64 or 256");
   CS_HIP(hipGetLastError());
   return CS_OK;
