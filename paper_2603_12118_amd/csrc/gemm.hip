@@ -223,9 +223,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 
   main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc);
 
+  // QKV: the (cos, sin) rows of this tile's BM tokens are staged in LDS (free after the K loop)
+  // with coalesced 16-byte loads; read per lane from global they are 16-byte pieces of 32 different
+  // rows per instruction, which cost 18 us of a 110 us launch.
+  [[maybe_unused]] int rope_stride = 0;
+  if constexpr (EPI == EPI_QKV) {
+    if (g.rope_cs) {
+      const int half = g.head_dim >> 1;
+      const int cpr = half >> 1;                       // 16-byte chunks per token row (two pairs each)
+      rope_stride = (cpr * 16 + 16) | 16;              // padded so that rows spread over the LDS banks
+      const int64_t last = (int64_t)M * cpr - 1;
+      __syncthreads();                                 // every wave is done reading the last K slice
+      for (int c = threadIdx.x; c < BM * cpr; c += 64 * WGM * WGN) {
+        int64_t src = (int64_t)m0 * cpr + c;
+        src = src < last ? src : last;
+        const f32x4 v = reinterpret_cast<const f32x4*>(g.rope_cs)[src];
+        *reinterpret_cast<f32x4*>(smem + (c / cpr) * rope_stride + (c % cpr) * 16) = v;
+      }
+      __syncthreads();
+    }
+  }
+
   // ---- epilogue.  Register 4q+e of lane l in block (i,j) is the element
   //      (row m = i*32 + l%32, column n = j*32 + 8q + 4*(l/32) + e).
   const int nw = n0 + wn * WN + 4 * lhi;
+  // QKV: byte offset of the first (cos, sin) pair of every 4-column group, once per lane (the
+  // divisions by run-time sizes must not be redone for every row block)
+  [[maybe_unused]] int rope_off[TN][4];
+  if constexpr (EPI == EPI_QKV) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = nw + j * 32 + 8 * q;
+        rope_off[j][q] = ((((n < g.hidden ? n : n - g.hidden)) % g.head_dim) >> 1) * 8;
+      }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wm * WM + i * 32 + l31;
@@ -257,7 +290,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     } else if constexpr (EPI == EPI_QKV) {
       // q and k columns: rotary on neighbouring columns (2p, 2p+1), both held by this lane
       bf16_t* orow = static_cast<bf16_t*>(g.out) + row * g.ldo;
-      const int half = g.head_dim >> 1;
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -269,8 +301,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
           float v0 = acc[i][j][4 * q] + b[0], v1 = acc[i][j][4 * q + 1] + b[1];
           float v2 = acc[i][j][4 * q + 2] + b[2], v3 = acc[i][j][4 * q + 3] + b[3];
           if (g.rope_cs) {
-            const int p = ((n % g.hidden) % g.head_dim) >> 1;   // first of the two rotary pairs held here
-            const f32x4 cs = *reinterpret_cast<const f32x4*>(g.rope_cs + ((int64_t)m * half + p) * 2);  // cos,sin,cos,sin
+            const f32x4 cs = *reinterpret_cast<const f32x4*>(smem + (m - m0) * rope_stride + rope_off[j][q]);  // cos,sin,cos,sin
             const float r0 = v0 * cs[0] - v1 * cs[1], r1 = v1 * cs[0] + v0 * cs[1];
             const float r2 = v2 * cs[2] - v3 * cs[3], r3 = v3 * cs[2] + v2 * cs[3];
             v0 = r0; v1 = r1; v2 = r2; v3 = r3;
