@@ -236,11 +236,12 @@ cs_status launch_attention(const AttnArgs& a, hipStream_t stream) {
   if (a.n_tok < 4 || a.ld_vt < ((a.n_tok + 3) & ~3)) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt too small");
   if (a.ld_vt & 3) return fail(CS_ERR_INVALID_ARG, "attention: ld_vt must be a multiple of 4");
   dim3 grid(a.n_work, a.n_heads);
-  // 64-query work items (window layers): two waves of 32 queries; 256-query items: four waves of 64
+  // every wave owns 32 queries: two waves per 64-query work item (window layers), eight per 256-query item,
+  // two waves per SIMD so that one wave's softmax arithmetic runs under the other's MFMAs
   if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 2, 1>), grid, dim3(128), 0, stream, a);
-  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 4, 2>), grid, dim3(256), 0, stream, a);
+  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 8, 1>), grid, dim3(512), 0, stream, a);
   else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 2, 1>), grid, dim3(128), 0, stream, a);
-  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 4, 2>), grid, dim3(256), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 8, 1>), grid, dim3(512), 0, stream, a);
   else return fail(CS_ERR_UNSUPPORTED, "attention: head_dim must be 64 or 80 and q_per_block 64 or 256");
   CS_HIP(hipGetLastError());
   return CS_OK;
