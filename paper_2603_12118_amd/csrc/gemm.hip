@@ -37,7 +37,73 @@ __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
   return __builtin_bit_cast(u32x2, h);
 }
 __device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// z * sigmoid(z) with the hardware exp2 and reciprocal (1 ulp each): five instructions, where the
+// IEEE division costs a dozen, and this runs for every element of the widest GEMM's epilogue
+__device__ __forceinline__ float silu_f(float z) {
+  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
+
+// ---- epilogue through LDS.  A lane of an accumulator block owns one row and 4-column groups of
+// it, so storing from registers writes 16-byte pieces of 32 different rows per instruction: measured,
+// that way the stores cost a quarter of a K = 1280 launch.  Instead every wave passes its blocks
+// through a private 32-row LDS chunk and writes them out as whole 64- or 128-byte row segments,
+// 16 bytes per lane.  LDS serves one wave's instructions in order, so no wait is needed between a
+// chunk's writes and reads beyond keeping the compiler from reordering them.
+constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
+constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
+
+// v[b][q] holds columns b*32 + 8q + 4*(lane/32) .. +3 of row lane%32 of a 32 x (NB*32) block.
+// The block's element (r, c) goes to out[rowmap(row0 + r) * ld + col0 + c] for row0 + r < row_end,
+// col0 + c < col_end (col_end - col0 a multiple of 4); ACCUM adds to what is there (fp32 only).
+template <int NB, typename T, bool ACCUM>
+__device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&v)[NB][4], T* out, int64_t ld,
+                                            const int32_t* row_map, int row0, int row_end, int col0, int col_end,
+                                            bool wide, const f32x4* held = nullptr) {
+  constexpr int ES = (int)sizeof(T);
+  static_assert(NB * 32 * ES <= 128, "a chunk row holds 128 bytes");
+  static_assert(!ACCUM || ES == 4, "accumulation is for fp32 outputs");
+  const int lane = threadIdx.x & 63, l31 = lane & 31, lhi = lane >> 5;
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      unsigned char* p = chunk + l31 * CHUNK_STRIDE + (b * 32 + 8 * q + 4 * lhi) * ES;
+      if constexpr (ES == 2) *reinterpret_cast<u32x2*>(p) = pack4(v[b][q][0], v[b][q][1], v[b][q][2], v[b][q][3]);
+      else *reinterpret_cast<f32x4*>(p) = v[b][q];
+    }
+  asm volatile("" ::: "memory");
+  constexpr int LPR = NB * 32 * ES / 16;          // lanes per row
+  constexpr int RPI = 64 / LPR;                   // rows per instruction
+  constexpr int EPL = 16 / ES;                    // elements per lane
+#pragma unroll
+  for (int it = 0; it < 32 / RPI; ++it) {
+    const int r = it * RPI + lane / LPR, c = (lane % LPR) * EPL;
+    const f32x4 piece = *reinterpret_cast<const f32x4*>(chunk + r * CHUNK_STRIDE + (lane % LPR) * 16);
+    const int m = row0 + r, n = col0 + c;
+    if (m >= row_end || n >= col_end) continue;
+    int64_t row = m;
+    if (row_map) {
+      row = row_map[m];
+      if (row < 0) continue;
+    }
+    T* dst = out + row * ld + n;
+    if constexpr (ES == 4) {
+      f32x4* d4 = reinterpret_cast<f32x4*>(dst);
+      if constexpr (ACCUM) *d4 = (held ? held[it] : *d4) + piece;
+      else *d4 = piece;
+    } else {
+      if (wide && n + 8 <= col_end) {
+        *reinterpret_cast<f32x4*>(dst) = piece;
+      } else {
+        const f32x2 lo = {piece[0], piece[1]}, hi = {piece[2], piece[3]};
+        *reinterpret_cast<f32x2*>(dst) = lo;
+        if (n + 8 <= col_end) *reinterpret_cast<f32x2*>(dst + 4) = hi;
+      }
+    }
+  }
+  asm volatile("" ::: "memory");
+}
 
 // Issues the LDS-direct loads of one 64-wide K slice: every wave instruction moves 64 x 16 bytes
 // from the lanes' global addresses to 1 KB of LDS starting at a wave-uniform address, in lane order.
@@ -63,19 +129,73 @@ __device__ __forceinline__ void issue_one(const bf16_t* const* ap, const bf16_t*
                                      (lds_void*)(uintptr_t)(stage + BM * 128 + ((l - A_LOADS) * NWAVES + wave) * 1024), 16, 0, 0);
 }
 
-// The K loop.  W_FIRST: accumulate C^T blocks (lane = row m, registers = columns n); otherwise
-// C blocks (lane = column n, registers = rows m).
-template <int BM, int BN, int WGM, int WGN, bool W_FIRST>
+// One 64-wide K slice of a wave's MFMAs.  PREFETCH: the loads of slice kn go out one at a time
+// between the MFMAs of the first k-steps: issued in one burst behind the barrier they queue in the
+// texture-address unit (16 clocks each, all waves at once) and every wave sits in the issue stall
+// instead of feeding the MFMA pipe.  W_FIRST: accumulate C^T blocks (lane = row m, registers =
+// columns n); otherwise C blocks (lane = column n, registers = rows m).
+template <int BM, int BN, int WGM, int WGN, bool W_FIRST, bool PREFETCH>
+__device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* const* bp, int kn,
+                                        const unsigned char* cur, unsigned char* nxt, int a_rd, int b_rd, int sw,
+                                        int lhi, int wave, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  constexpr int NWAVES = WGM * WGN;
+  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
+  constexpr int RD_PER = 2;     // LDS reads of the next k-step issued behind each of the first MFMAs
+  constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
+  bf16x8 af[2][TM], bfr[2][TN];
+  {
+    const int coff = (lhi ^ sw) << 4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(cur + a_rd + i * 32 * 128 + coff);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(cur + b_rd + j * 32 * 128 + coff);
+  }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    // MFMAs of k-step ks in source order, two LDS reads of k-step ks+1 behind each of the first
+    // ones; the scheduling barriers keep the compiler from regrouping them, so the reads'
+    // latency is covered by the MFMAs that follow.
+    const int coff = (((ks + 1) * 2 + lhi) ^ sw) << 4;
+#pragma unroll
+    for (int n = 0; n < TM * TN; ++n) {
+      const int i = n / TN, j = n % TN;
+      if (W_FIRST)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+      else
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+      if (PREFETCH && ks < SPREAD_KS) {
+        constexpr int LT = A_LOADS + B_LOADS, SLOTS = SPREAD_KS * TM * TN;
+#pragma unroll
+        for (int l = 0; l < LT; ++l)
+          if (l * SLOTS / LT == ks * TM * TN + n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
+      }
+      if (ks < 3) {
+#pragma unroll
+        for (int q = RD_PER * n; q < RD_PER * n + RD_PER && q < TM + TN; ++q) {
+          if (q == 0) af[(ks + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(cur + a_rd + coff);
+          else if (q <= TN) bfr[(ks + 1) & 1][q - 1] = *reinterpret_cast<const bf16x8*>(cur + b_rd + (q - 1) * 32 * 128 + coff);
+          else af[(ks + 1) & 1][q - TN] = *reinterpret_cast<const bf16x8*>(cur + a_rd + (q - TN) * 32 * 128 + coff);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// The K loop.  On return the stage buffer that does not hold the last slice is idle: every wave
+// passed the last barrier after reading it and nothing was loaded into it since.
+// before_last() runs between the last barrier and the last slice's MFMAs: global loads it issues
+// are in flight while those execute.
+template <int BM, int BN, int WGM, int WGN, bool W_FIRST, typename F>
 __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem, int m0, int n0,
-                                          f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
+                                          f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], F&& before_last) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
-  constexpr int RD_PER = 2;  // LDS reads of the next k-step issued behind each of the first MFMAs
-  constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N, K = g.K;
@@ -110,63 +230,32 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   }
   const int KT = K >> 6;
   issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
-  for (int kt = 0; kt < KT; ++kt) {
+  for (int kt = 0; kt < KT - 1; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's part of slice kt has landed
     __syncthreads();                                    // ... and everyone's; slice kt-1 fully consumed
-    // The loads of slice kt+1 go out one at a time between the MFMAs of the first k-steps: issued
-    // in one burst behind the barrier they queue in the texture-address unit (16 clocks each, all
-    // waves at once) and every wave sits in the issue stall instead of feeding the MFMA pipe.
-    // The last iteration re-reads slice kt into the idle buffer: no branch around the loads.
-    const int kn = kt + 1 < KT ? kt + 1 : kt;
-    bf16x8 af[2][TM], bfr[2][TN];
-    {
-      const int coff = (lhi ^ sw) << 4;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8*>(cur + a_rd + i * 32 * 128 + coff);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8*>(cur + b_rd + j * 32 * 128 + coff);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      // MFMAs of k-step ks in source order, two LDS reads of k-step ks+1 behind each of the first
-      // ones; the scheduling barriers keep the compiler from regrouping them, so the reads'
-      // latency is covered by the MFMAs that follow.
-      const int coff = (((ks + 1) * 2 + lhi) ^ sw) << 4;
-#pragma unroll
-      for (int n = 0; n < TM * TN; ++n) {
-        const int i = n / TN, j = n % TN;
-        if (W_FIRST)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
-        else
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-        if (ks < SPREAD_KS) {
-          constexpr int LT = A_LOADS + B_LOADS, SLOTS = SPREAD_KS * TM * TN;
-#pragma unroll
-          for (int l = 0; l < LT; ++l)
-            if (l * SLOTS / LT == ks * TM * TN + n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
-        }
-        if (ks < 3) {
-#pragma unroll
-          for (int q = RD_PER * n; q < RD_PER * n + RD_PER && q < TM + TN; ++q) {
-            if (q == 0) af[(ks + 1) & 1][0] = *reinterpret_cast<const bf16x8*>(cur + a_rd + coff);
-            else if (q <= TN) bfr[(ks + 1) & 1][q - 1] = *reinterpret_cast<const bf16x8*>(cur + b_rd + (q - 1) * 32 * 128 + coff);
-            else af[(ks + 1) & 1][q - TN] = *reinterpret_cast<const bf16x8*>(cur + a_rd + (q - TN) * 32 * 128 + coff);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+    k_slice<BM, BN, WGM, WGN, W_FIRST, true>(ap, bp, kt + 1, cur, nxt, a_rd, b_rd, sw, lhi, wave, acc);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the redundant last prefetch lands before LDS is released
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  before_last();
+  k_slice<BM, BN, WGM, WGN, W_FIRST, false>(ap, bp, 0, smem + ((KT - 1) & 1) * STAGE_BYTES, nullptr, a_rd, b_rd, sw, lhi,
+                                            wave, acc);
 }
+
+template <int V>
+struct int_tag { static constexpr int value = V; };
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int STAGE_BYTES = (BM + BN) * 128;
+  constexpr int NWAVES = WGM * WGN;
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
+  static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
+  static_assert(NWAVES * CHUNK_BYTES <= STAGE_BYTES, "the epilogue chunks live in the idle stage buffer");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -193,39 +282,71 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
 
   f32x16 acc[TM][TN];
+  // this wave's epilogue chunk, in the stage buffer the last K slice did not use
+  unsigned char* chunk = smem + ((g.K >> 6) & 1) * STAGE_BYTES + wave * CHUNK_BYTES;
 
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= 2 * g.hidden) {
       // v columns (the whole workgroup: 2*hidden is a multiple of BN).  Untransposed blocks: lane =
-      // column n = one v dimension, registers = rows, four consecutive tokens per register group,
-      // stored as 8 bytes into the transposed v buffer.
-      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc);
-      const int mw = m0 + wm * WM + 4 * lhi;
+      // column n = one v dimension, registers = rows (tokens); written as rows of the transposed
+      // v buffer, 64 tokens of one dimension per chunk row.
+      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [] {});
+      const bool wide = (g.ld_vt & 7) == 0;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn * WN + j * 32 + l31;
-        if (n >= N) continue;
-        const float b = g.bias ? g.bias[n] : 0.f;
-        bf16_t* dst = g.vt + (int64_t)(n - 2 * g.hidden) * g.ld_vt;
+        const float b = (g.bias && n < N) ? g.bias[n] : 0.f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; i += 2) {
+          f32x4 v[2][4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int m = mw + i * 32 + 8 * q;
-            if (m < M)
-              *reinterpret_cast<u32x2*>(dst + m) = pack4(acc[i][j][4 * q] + b, acc[i][j][4 * q + 1] + b,
-                                                         acc[i][j][4 * q + 2] + b, acc[i][j][4 * q + 3] + b);
-          }
+          for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * q + e] + b;
+          store_block<2, bf16_t, false>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
+                                        N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide);
+        }
       }
       return;
     }
   }
 
-  main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc);
+  // Residual add: the old values are needed in the epilogue, where a load's latency would be
+  // paid once per chunk (the stores in between keep the compiler from hoisting the loads).  With
+  // four waves per workgroup (one per SIMD, or small tiles) the registers for the whole wave tile
+  // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
+  constexpr bool HOLD = EPI == EPI_RESADD_F32 && NWAVES <= 4;
+  [[maybe_unused]] f32x4 held[HOLD ? TM : 1][HOLD ? TN : 1][4];
+  main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
+    if constexpr (HOLD) {
+      const int r = lane >> 3, c = (lane & 7) * 4;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          int m = m0 + wm * WM + i * 32 + it * 8 + r;
+          m = m < M ? m : M - 1;
+          int64_t row = m;
+          if (g.row_map) {
+            row = g.row_map[m];
+            row = row < 0 ? 0 : row;
+          }
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            int n = n0 + wn * WN + j * 32 + c;
+            n = n < N ? n : N - 4;
+            held[i][j][it] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.out) + row * g.ldo + n);
+          }
+        }
+    }
+  });
 
   // QKV: the (cos, sin) rows of this tile's BM tokens are staged in LDS (free after the K loop)
   // with coalesced 16-byte loads; read per lane from global they are 16-byte pieces of 32 different
-  // rows per instruction, which cost 18 us of a 110 us launch.
+  // rows per instruction, which cost 18 us of a 110 us launch.  The table sits at the bottom of
+  // LDS and the epilogue chunks move to the top.
   [[maybe_unused]] int rope_stride = 0;
   if constexpr (EPI == EPI_QKV) {
     if (g.rope_cs) {
@@ -233,6 +354,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       const int cpr = half >> 1;                       // 16-byte chunks per token row (two pairs each)
       rope_stride = (cpr * 16 + 16) | 16;              // padded so that rows spread over the LDS banks
       const int64_t last = (int64_t)M * cpr - 1;
+      chunk = smem + 2 * STAGE_BYTES - (NWAVES - wave) * CHUNK_BYTES;
       __syncthreads();                                 // every wave is done reading the last K slice
       for (int c = threadIdx.x; c < BM * cpr; c += 64 * WGM * WGN) {
         int64_t src = (int64_t)m0 * cpr + c;
@@ -246,7 +368,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 
   // ---- epilogue.  Register 4q+e of lane l in block (i,j) is the element
   //      (row m = i*32 + l%32, column n = j*32 + 8q + 4*(l/32) + e).
-  const int nw = n0 + wn * WN + 4 * lhi;
+  const int nw = n0 + wn * WN;               // first column of this wave
+  const int nl = nw + 4 * lhi;               // first column this lane holds
+  const bool wide = (g.ldo & 7) == 0;
   // QKV: byte offset of the first (cos, sin) pair of every 4-column group, once per lane (the
   // divisions by run-time sizes must not be redone for every row block)
   [[maybe_unused]] int rope_off[TN][4];
@@ -255,90 +379,105 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = nw + j * 32 + 8 * q;
+        const int n = nl + j * 32 + 8 * q;
         rope_off[j][q] = ((((n < g.hidden ? n : n - g.hidden)) % g.head_dim) >> 1) * 8;
       }
   }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * WM + i * 32 + l31;
-    if (m >= M) continue;
-    int64_t row = m;
-    if (g.row_map) {
-      row = g.row_map[m];
-      if (row < 0) continue;
-    }
+    const int mrow = m0 + wm * WM + i * 32;  // first row of the block
+    if (mrow >= M) continue;                 // wave-uniform
     if constexpr (EPI == EPI_SWIGLU_BF16) {
-      bf16_t* orow = static_cast<bf16_t*>(g.out) + row * g.ldo;
+      // output column p*32 + c of the wave pairs gate column 2p*32 + c with up column (2p+1)*32 + c
+      auto emit = [&](auto tag, int p0) {
+        constexpr int NB = decltype(tag)::value;
+        f32x4 v[NB][4];
 #pragma unroll
-      for (int j = 0; j < TN; j += 2)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int ng = nw + j * 32 + 8 * q;         // gate columns ng..ng+3, up columns 32 further
-          if (ng + 36 > N) continue;
-          f32x4 bg = {0.f, 0.f, 0.f, 0.f}, bu = {0.f, 0.f, 0.f, 0.f};
-          if (g.bias) {
-            bg = *reinterpret_cast<const f32x4*>(g.bias + ng);
-            bu = *reinterpret_cast<const f32x4*>(g.bias + ng + 32);
+          for (int q = 0; q < 4; ++q) {
+            const int j = 2 * (p0 + b);
+            const int ng = nl + j * 32 + 8 * q;       // gate columns ng..ng+3, up columns 32 further
+            f32x4 bg = {0.f, 0.f, 0.f, 0.f}, bu = {0.f, 0.f, 0.f, 0.f};
+            if (g.bias && ng + 36 <= N) {
+              bg = *reinterpret_cast<const f32x4*>(g.bias + ng);
+              bu = *reinterpret_cast<const f32x4*>(g.bias + ng + 32);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[b][q][e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
           }
-          float o[4];
+        store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M,
+                                       (nw >> 1) + p0 * 32, N >> 1, wide);
+      };
+      constexpr int NP = TN / 2;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
-          const int jo = ((n0 + wn * WN + j * 32) >> 1) + 4 * lhi + 8 * q;
-          *reinterpret_cast<u32x2*>(orow + jo) = pack4(o[0], o[1], o[2], o[3]);
-        }
-    } else if constexpr (EPI == EPI_QKV) {
-      // q and k columns: rotary on neighbouring columns (2p, 2p+1), both held by this lane
-      bf16_t* orow = static_cast<bf16_t*>(g.out) + row * g.ldo;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = nw + j * 32 + 8 * q;
-          if (n >= N) continue;
-          f32x4 b = {0.f, 0.f, 0.f, 0.f};
-          if (g.bias) b = *reinterpret_cast<const f32x4*>(g.bias + n);
-          float v0 = acc[i][j][4 * q] + b[0], v1 = acc[i][j][4 * q + 1] + b[1];
-          float v2 = acc[i][j][4 * q + 2] + b[2], v3 = acc[i][j][4 * q + 3] + b[3];
-          if (g.rope_cs) {
-            const f32x4 cs = *reinterpret_cast<const f32x4*>(smem + (m - m0) * rope_stride + rope_off[j][q]);  // cos,sin,cos,sin
-            const float r0 = v0 * cs[0] - v1 * cs[1], r1 = v1 * cs[0] + v0 * cs[1];
-            const float r2 = v2 * cs[2] - v3 * cs[3], r3 = v3 * cs[2] + v2 * cs[3];
-            v0 = r0; v1 = r1; v2 = r2; v3 = r3;
-          }
-          const float sc = n < g.hidden ? g.q_scale : 1.0f;
-          *reinterpret_cast<u32x2*>(orow + n) = pack4(v0 * sc, v1 * sc, v2 * sc, v3 * sc);
-        }
+      for (int p0 = 0; p0 + 1 < NP; p0 += 2) emit(int_tag<2>{}, p0);
+      if constexpr (NP & 1) emit(int_tag<1>{}, NP - 1);
     } else {
+      constexpr bool OUT_F32 = EPI == EPI_F32 || EPI == EPI_GELU_F32 || EPI == EPI_RESADD_F32;
+      auto emit = [&](auto tag, int j0) {
+        constexpr int NB = decltype(tag)::value;
+        f32x4 v[NB][4];
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = nw + j * 32 + 8 * q;
-          if (n >= N) continue;
-          f32x4 v;
+          for (int q = 0; q < 4; ++q) {
+            const int j = j0 + b;
+            const int n = nl + j * 32 + 8 * q;
+            f32x4 t;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-          if (g.bias) v += *reinterpret_cast<const f32x4*>(g.bias + n);
-          if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
+            for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
+            if (g.bias && n < N) t += *reinterpret_cast<const f32x4*>(g.bias + n);
+            if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+              for (int e = 0; e < 4; ++e) t[e] = gelu_erf(t[e]);
+            }
+            if constexpr (EPI == EPI_QKV) {
+              // q and k columns: rotary on neighbouring columns (2p, 2p+1), both held by this lane
+              if (g.rope_cs) {
+                const f32x4 cs = *reinterpret_cast<const f32x4*>(smem + (mrow - m0 + l31) * rope_stride + rope_off[j][q]);  // cos,sin,cos,sin
+                const float r0 = t[0] * cs[0] - t[1] * cs[1], r1 = t[1] * cs[0] + t[0] * cs[1];
+                const float r2 = t[2] * cs[2] - t[3] * cs[3], r3 = t[3] * cs[2] + t[2] * cs[3];
+                t[0] = r0; t[1] = r1; t[2] = r2; t[3] = r3;
+              }
+              t *= n < g.hidden ? g.q_scale : 1.0f;
+            }
+            v[b][q] = t;
           }
+        const int col0 = nw + j0 * 32;
+        if constexpr (EPI == EPI_RESADD_F32) {
+          store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true,
+                                       HOLD ? held[i][j0] : nullptr);
+        } else if constexpr (OUT_F32) {
+          store_block<NB, float, false>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true);
+        } else if constexpr (EPI == EPI_QKV) {
+          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0,
+                                         2 * g.hidden, wide);
+        } else {
+          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide);
           if constexpr (EPI == EPI_GELU_SPLIT) {
-            bf16_t* o = static_cast<bf16_t*>(g.out) + row * g.ldo + n;
-            const u32x2 hi = pack4(v[0], v[1], v[2], v[3]);
-            *reinterpret_cast<u32x2*>(o) = hi;
-            *reinterpret_cast<u32x2*>(o + N) = pack4(v[0] - __uint_as_float(hi.x << 16), v[1] - __uint_as_float(hi.x & 0xFFFF0000u),
-                                                     v[2] - __uint_as_float(hi.y << 16), v[3] - __uint_as_float(hi.y & 0xFFFF0000u));
-          } else if constexpr (EPI == EPI_BF16 || EPI == EPI_GELU_BF16) {
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.out) + row * g.ldo + n) = pack4(v[0], v[1], v[2], v[3]);
-          } else if constexpr (EPI == EPI_RESADD_F32) {
-            f32x4* p = reinterpret_cast<f32x4*>(static_cast<float*>(g.out) + row * g.ldo + n);
-            *p = *p + v;
-          } else {
-            *reinterpret_cast<f32x4*>(static_cast<float*>(g.out) + row * g.ldo + n) = v;
+            // second half of the row: what the bf16 rounding of the first half dropped
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const bf16x4 h = __builtin_convertvector(v[b][q], bf16x4);
+                v[b][q] -= __builtin_convertvector(h, f32x4);
+              }
+            store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, N,
+                                           wide && (N & 7) == 0);
           }
         }
+      };
+      constexpr int PER = OUT_F32 ? 1 : 2;   // 32-column blocks per 128-byte chunk row
+      if constexpr (PER == 2) {
+#pragma unroll
+        for (int j0 = 0; j0 + 1 < TN; j0 += 2) emit(int_tag<2>{}, j0);
+        if constexpr (TN & 1) emit(int_tag<1>{}, TN - 1);
+      } else {
+#pragma unroll
+        for (int j0 = 0; j0 < TN; ++j0) emit(int_tag<1>{}, j0);
+      }
     }
   }
 }
@@ -396,6 +535,8 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream) {
       if ((g.M & 3) || (g.hidden & 63) || (g.head_dim & 3) || g.N != 3 * g.hidden || (g.ld_vt & 3) ||
           (reinterpret_cast<uintptr_t>(g.vt) & 7))
         return fail(CS_ERR_UNSUPPORTED, "gemm: qkv epilogue needs M % 4 == 0, hidden % 64 == 0, head_dim % 4 == 0, N == 3 hidden");
+      // the (cos, sin) table of a tile's tokens and the epilogue chunks share LDS behind the K loop
+      if (g.rope_cs && g.head_dim > 84) return fail(CS_ERR_UNSUPPORTED, "gemm: rotary epilogue needs head_dim <= 84");
       return launch_epi<EPI_QKV>(g, stream);
     default: return fail(CS_ERR_INVALID_ARG, "gemm: unknown epilogue");
   }
