@@ -290,12 +290,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       // v columns (the whole workgroup: 2*hidden is a multiple of BN).  Untransposed blocks: lane =
       // column n = one v dimension, registers = rows (tokens); written as rows of the transposed
       // v buffer, 64 tokens of one dimension per chunk row.
-      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [] {});
+      float bv[TN];
+      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [&] {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int n = n0 + wn * WN + j * 32 + l31;
+          bv[j] = (g.bias && n < N) ? g.bias[n] : 0.f;
+        }
+      });
       const bool wide = (g.ld_vt & 7) == 0;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + l31;
-        const float b = (g.bias && n < N) ? g.bias[n] : 0.f;
+        const float b = bv[j];
 #pragma unroll
         for (int i = 0; i < TM; i += 2) {
           f32x4 v[2][4];
@@ -319,7 +325,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
   constexpr bool HOLD = EPI == EPI_RESADD_F32 && NWAVES <= 4;
   [[maybe_unused]] f32x4 held[HOLD ? TM : 1][HOLD ? TN : 1][4];
+  // The bias of the lane's columns is fetched there too (a load inside the epilogue waits out its
+  // latency once per chunk).
+  f32x4 bias_r[TN][4];
   main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WN + 4 * lhi + j * 32 + 8 * q;
+        bias_r[j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (g.bias && n < N) bias_r[j][q] = *reinterpret_cast<const f32x4*>(g.bias + n);
+      }
     if constexpr (HOLD) {
       const int r = lane >> 3, c = (lane & 7) * 4;
 #pragma unroll
@@ -351,17 +368,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   if constexpr (EPI == EPI_QKV) {
     if (g.rope_cs) {
       const int half = g.head_dim >> 1;
-      const int cpr = half >> 1;                       // 16-byte chunks per token row (two pairs each)
-      rope_stride = (cpr * 16 + 16) | 16;              // padded so that rows spread over the LDS banks
-      const int64_t last = (int64_t)M * cpr - 1;
+      const int cpr = half >> 1;                       // 16-byte pieces per token row (two pairs each)
+      const int upr = (cpr + 1) | 1;                   // ... per padded LDS row: odd, so rows spread over the banks
+      rope_stride = upr * 16;
       chunk = smem + 2 * STAGE_BYTES - (NWAVES - wave) * CHUNK_BYTES;
       __syncthreads();                                 // every wave is done reading the last K slice
-      for (int c = threadIdx.x; c < BM * cpr; c += 64 * WGM * WGN) {
-        int64_t src = (int64_t)m0 * cpr + c;
-        src = src < last ? src : last;
-        const f32x4 v = reinterpret_cast<const f32x4*>(g.rope_cs)[src];
-        *reinterpret_cast<f32x4*>(smem + (c / cpr) * rope_stride + (c % cpr) * 16) = v;
+      // LDS-direct loads, all in flight at once: piece u of the padded table comes from row u / upr
+      // (the padding pieces repeat the row's last one; the tail of the last instruction runs up to
+      // 1 KB past the table, below the chunks)
+      for (int base = wave * 64; base < BM * upr; base += 64 * NWAVES) {
+        const int u = base + lane;
+        int r = u / upr, c = u - r * upr;
+        c = c < cpr ? c : cpr - 1;
+        r = m0 + r < M ? m0 + r : M - 1;
+        __builtin_amdgcn_global_load_lds(g.rope_cs + ((int64_t)r * cpr + c) * 4, (lds_void*)(uintptr_t)(smem + base * 16), 16, 0, 0);
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
     }
   }
@@ -397,12 +419,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int j = 2 * (p0 + b);
-            const int ng = nl + j * 32 + 8 * q;       // gate columns ng..ng+3, up columns 32 further
-            f32x4 bg = {0.f, 0.f, 0.f, 0.f}, bu = {0.f, 0.f, 0.f, 0.f};
-            if (g.bias && ng + 36 <= N) {
-              bg = *reinterpret_cast<const f32x4*>(g.bias + ng);
-              bu = *reinterpret_cast<const f32x4*>(g.bias + ng + 32);
-            }
+            const f32x4 bg = bias_r[j][q], bu = bias_r[j + 1][q];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[b][q][e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
           }
@@ -427,7 +444,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
             f32x4 t;
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
-            if (g.bias && n < N) t += *reinterpret_cast<const f32x4*>(g.bias + n);
+            t += bias_r[j][q];
             if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) t[e] = gelu_erf(t[e]);
@@ -536,7 +553,7 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream) {
           (reinterpret_cast<uintptr_t>(g.vt) & 7))
         return fail(CS_ERR_UNSUPPORTED, "gemm: qkv epilogue needs M % 4 == 0, hidden % 64 == 0, head_dim % 4 == 0, N == 3 hidden");
       // the (cos, sin) table of a tile's tokens and the epilogue chunks share LDS behind the K loop
-      if (g.rope_cs && g.head_dim > 84) return fail(CS_ERR_UNSUPPORTED, "gemm: rotary epilogue needs head_dim <= 84");
+      if (g.rope_cs && g.head_dim > 80) return fail(CS_ERR_UNSUPPORTED, "gemm: rotary epilogue needs head_dim <= 80");
       return launch_epi<EPI_QKV>(g, stream);
     default: return fail(CS_ERR_INVALID_ARG, "gemm: unknown epilogue");
   }
