@@ -617,9 +617,9 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     {
       StepTimer tm(e, full ? CS_STEP_ATTN_FULL : CS_STEP_ATTN_WINDOW, stream);
       if (full) {
-        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256;
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256; aa.single_tile = 0;
       } else {
-        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64;
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64; aa.single_tile = p.win_single_tile;
       }
       if (cs_status st = launch_attention(aa, stream)) return st;
     }
@@ -706,7 +706,7 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
     AttnArgs a = {};
     a.qk = static_cast<const bf16_t*>(qk); a.vt = static_cast<const bf16_t*>(vt); a.ld_vt = ld_vt;
     a.out = static_cast<bf16_t*>(out); a.work = dwork; a.n_work = (int32_t)(work.size() / 4);
-    a.n_tok = seg_cu[n_seg]; a.n_heads = n_heads; a.head_dim = head_dim; a.q_per_block = qpb;
+    a.n_tok = seg_cu[n_seg]; a.n_heads = n_heads; a.head_dim = head_dim; a.q_per_block = qpb; a.single_tile = max_len <= 64;
     st = launch_attention(a, stream);
     (void)hipStreamSynchronize(stream);
   }

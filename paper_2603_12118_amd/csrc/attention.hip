@@ -26,8 +26,14 @@ __device__ __forceinline__ uint32_t pack2_a(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_a));
 }
 
-template <int DH, int NW, int QT>
-__global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
+// Window layers launch thousands of two-wave workgroups, each a short chain load -> stage ->
+// MFMA -> store: latency is hidden only by residency, so the single-tile variant is held to 168 registers
+// (three waves per SIMD, six workgroups per CU, which is also what their LDS tiles allow).
+// SINGLE: every work item has at most 64 keys (windows of up to 64 tokens): one tile, nothing to
+// prefetch, so the staging registers are dead before the accumulators come alive.
+template <int DH, int NW, int QT, bool SINGLE>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SINGLE ? 3 : 2, SINGLE ? 3 : 2)))
+void attn_kernel(AttnArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int KS = DH / 16;            // k-steps of the score product
   constexpr int DT = (DH + 31) / 32;     // 32-row tiles of O^T
@@ -117,11 +123,11 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
   };
 
   load_tile(w.kv0);
-  for (int kv = w.kv0; kv < w.kv1; kv += 64) {
-    __syncthreads();  // previous tile fully consumed
+  for (int kv = w.kv0; kv < (SINGLE ? w.kv0 + 1 : w.kv1); kv += 64) {
+    if (!SINGLE) __syncthreads();  // previous tile fully consumed
     store_tile();
     __syncthreads();
-    if (kv + 64 < w.kv1) load_tile(kv + 64);
+    if (!SINGLE && kv + 64 < w.kv1) load_tile(kv + 64);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
@@ -238,10 +244,13 @@ cs_status launch_attention(const AttnArgs& a, hipStream_t stream) {
   dim3 grid(a.n_work, a.n_heads);
   // every wave owns 32 queries: two waves per 64-query work item (window layers), eight per 256-query item,
   // two waves per SIMD so that one wave's softmax arithmetic runs under the other's MFMAs
-  if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 2, 1>), grid, dim3(128), 0, stream, a);
-  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 8, 1>), grid, dim3(512), 0, stream, a);
-  else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 2, 1>), grid, dim3(128), 0, stream, a);
-  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 8, 1>), grid, dim3(512), 0, stream, a);
+  if (a.single_tile && a.q_per_block != 64) return fail(CS_ERR_INVALID_ARG, "attention: single-tile items are 64-query items");
+  if (a.head_dim == 80 && a.q_per_block == 64 && a.single_tile) hipLaunchKernelGGL((attn_kernel<80, 2, 1, true>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 80 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<80, 2, 1, false>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 80 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<80, 8, 1, false>), grid, dim3(512), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 64 && a.single_tile) hipLaunchKernelGGL((attn_kernel<64, 2, 1, true>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 64) hipLaunchKernelGGL((attn_kernel<64, 2, 1, false>), grid, dim3(128), 0, stream, a);
+  else if (a.head_dim == 64 && a.q_per_block == 256) hipLaunchKernelGGL((attn_kernel<64, 8, 1, false>), grid, dim3(512), 0, stream, a);
   else return fail(CS_ERR_UNSUPPORTED, "attention: head_dim must be 64 or 80 and q_per_block 64 or 256");
   CS_HIP(hipGetLastError());
   return CS_OK;

@@ -68,6 +68,7 @@ struct AttnArgs {
   const AttnWork* work;
   int32_t n_work, n_tok, n_heads, head_dim;
   int32_t q_per_block;  // 64 or 256 queries per workgroup (work items are cut accordingly)
+  int32_t single_tile;  // nonzero: no work item has more than 64 keys (64-query items only)
 };
 cs_status launch_attention(const AttnArgs& a, hipStream_t stream);
 

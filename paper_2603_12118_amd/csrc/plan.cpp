@@ -60,6 +60,7 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
   pos.reserve(3 * N);
   out_row.reserve(p.n_out);
   p.win_cu.assign(1, 0);
+  p.win_single_tile = true;
   int64_t out_base = 0;
   for (int i = 0; i < n_items; ++i) {
     const int T = grid[3 * i], h = grid[3 * i + 1], w = grid[3 * i + 2];
@@ -84,6 +85,7 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
           if (cfg.window > 0) {
             const int w0 = p.win_cu.back(), w1 = (int)src_row.size();
             p.win_cu.push_back(w1);
+            if (w1 - w0 > 64) p.win_single_tile = false;
             for (int q = w0; q < w1; q += 64) push_work(win_work, q, std::min(q + 64, w1), w0, w1);
           }
         }

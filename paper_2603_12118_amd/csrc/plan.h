@@ -20,6 +20,7 @@ struct BatchPlan {
   size_t off_win_work = 0;  // [n_win_work*4] AttnWork, one window (or 64-query slice of it) each
   size_t off_full_work = 0; // [n_full_work*4] AttnWork, 256-query blocks of whole items
   int32_t n_win_work = 0, n_full_work = 0;
+  bool win_single_tile = false;  // no window has more than 64 tokens
   std::vector<int32_t> win_cu;  // host only: window boundaries in internal token order
   // audio
   int64_t n_pad_rows = 0;   // sum(frames_i + 2): rows of the zero-padded frame buffers
