@@ -16,6 +16,10 @@ import numpy as np
 
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 flop/CU/clk, dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per launch of the gate|up GEMM on c2_images from the FETCH_SIZE / WRITE_SIZE counter
+# runs summarised in profiles/c2_images_hbm_counters.md: (110271 KiB x 2.00 + 55296 KiB x 1.00) x 1024.
+# Valid for the kernel those counters were taken on; set to None when gemm.hip changes.
+GATE_UP_TRAFFIC_BYTES = {"c2_images": (110271 * 2.00 + 55296 * 1.00) * 1024}
 
 
 def algorithmic_flops(cfg, grid_thw) -> dict:
@@ -134,7 +138,7 @@ def main() -> int:
         "roofline": {"kernel": "gemm_kernel<256,256,2,4,SWIGLU> (gate|up projection)" if w.cfg.arch == "vit"
                      else "gemm_kernel<256,256,2,4,GELU> (fc1)", "bound": "mfma",
                      "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": GATE_UP_TRAFFIC_BYTES.get(w.name),
                      "avg_launch_ms": dom_avg_ms, "launches_timed": dom_n, "flop_per_launch": dom_flops},
         "setup_s": setup_s,
     }
