@@ -171,8 +171,11 @@ void attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[it][jt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      // v_exp_f32 directly: arguments are <= 0 and results that would be denormal may flush to 0,
+      // so the library exp2f's range scaling (four more instructions per score) buys nothing here
       const float mnew = fmaxf(mrun[it], mx);      // finite: every tile holds at least one valid key
-      const float alpha = exp2f(mrun[it] - mnew);
+      const float alpha = __builtin_amdgcn_exp2f(mrun[it] - mnew);
+      const bool moved = __any(mnew != mrun[it]);  // some query of this wave has a new maximum
       mrun[it] = mnew;
       float sum = 0.f;
 #pragma unroll
@@ -182,8 +185,8 @@ void attn_kernel(AttnArgs a) {
           uint32_t pk[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p0 = exp2f(s[it][jt][8 * u + 2 * e] - mnew);
-            const float p1 = exp2f(s[it][jt][8 * u + 2 * e + 1] - mnew);
+            const float p0 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e] - mnew);
+            const float p1 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e + 1] - mnew);
             sum += p0 + p1;
             pk[e] = pack2_a(p0, p1);
           }
@@ -191,10 +194,12 @@ void attn_kernel(AttnArgs a) {
           pf[it][jt * 2 + u] = *reinterpret_cast<bf16x8*>(&t);
         }
       lrun[it] = lrun[it] * alpha + sum;
+      if (moved) {                                 // otherwise alpha is exactly 1 in every lane
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[it][dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) o[it][dt][r] *= alpha;
+      }
     }
     // ---- O^T += V^T P^T.  k-slot e of lane-half lhi in step (jt,u) is key jt*32 + 16u + 8*(e/4) + 4*lhi + e%4
 #pragma unroll
