@@ -206,6 +206,16 @@ typedef enum {
 cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
 cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
 
+/* Measurement aid: the rate of a bare v_mfma_f32_32x32x16_bf16 loop (no memory traffic) on the
+ * current device, the ceiling the GEMMs' roofline fraction is read against.  Runs one warm-up and
+ * one timed launch of 256 workgroups x 8 waves x iters x 32 MFMAs on `stream`, waits for it, and
+ * writes TFLOP/s to *tflops (host).  random_operands = 0: all operands zero (nominal clock);
+ * otherwise pseudo-random operands in [-1, 1], with which the board runs into its power limit.
+ *  scratch  dev, at least 512 KiB (the accumulators are stored there so the loop is not removed).
+ * Errors: CS_ERR_INVALID_ARG for NULL / small scratch or iters <= 0; CS_ERR_HIP from the runtime. */
+cs_status cs_mfma_ceiling(void* scratch, size_t scratch_bytes, int32_t random_operands, int32_t iters,
+                          double* tflops, void* stream);
+
 const char* cs_status_string(cs_status s);
 const char* cs_last_error(void);
 

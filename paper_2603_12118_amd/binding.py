@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
         L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
         L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
         L.cs_encoder_read_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.cs_status_string.argtypes = [C.c_int]
@@ -221,6 +222,16 @@ def cs_attention_varlen(qk, vt, out, seg_cu: Sequence[int], n_heads: int, head_d
     seg = _i32(seg_cu)
     _check(lib().cs_attention_varlen(qk.data_ptr(), vt.data_ptr(), vt.stride(0), out.data_ptr(), _i32p(seg),
                                      len(seg) - 1, n_heads, head_dim, _stream(stream)))
+
+
+def cs_mfma_ceiling(random_operands: bool, iters: int = 8000, stream=None) -> float:
+    """TFLOP/s of a bare MFMA loop on the current device (see cornenc.h)."""
+    import torch
+    scratch = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    out = C.c_double(0.0)
+    _check(lib().cs_mfma_ceiling(scratch.data_ptr(), scratch.numel() * 4, int(bool(random_operands)), int(iters),
+                                 C.byref(out), _stream(stream)))
+    return out.value
 
 
 def last_error() -> str:

@@ -714,4 +714,30 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
   return st;
 }
 
+cs_status cs_mfma_ceiling(void* scratch, size_t scratch_bytes, int32_t random_operands, int32_t iters, double* tflops,
+                          void* stream_) {
+  constexpr int kBlocks = 256;
+  if (!scratch || !tflops || iters <= 0 || scratch_bytes < (size_t)kBlocks * 512 * 4)
+    return fail(CS_ERR_INVALID_ARG, "cs_mfma_ceiling: scratch of at least 512 KiB, iters > 0");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  CS_HIP(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CS_ERR_HIP, "hipEventCreate"); }
+  cs_status st = launch_mfma_loop(static_cast<float*>(scratch), kBlocks, 16, random_operands, stream);
+  float ms = 0.f;
+  if (st == CS_OK) {
+    hipError_t he = hipEventRecord(e0, stream);
+    if (he == hipSuccess) st = launch_mfma_loop(static_cast<float*>(scratch), kBlocks, iters, random_operands, stream);
+    if (he == hipSuccess && st == CS_OK) he = hipEventRecord(e1, stream);
+    if (he == hipSuccess && st == CS_OK) he = hipEventSynchronize(e1);
+    if (he == hipSuccess && st == CS_OK) he = hipEventElapsedTime(&ms, e0, e1);
+    if (he != hipSuccess) st = fail(CS_ERR_HIP, hipGetErrorString(he));
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (st != CS_OK) return st;
+  *tflops = (double)kBlocks * 8 * iters * 32 * 32768.0 / ((double)ms * 1e-3) / 1e12;
+  return CS_OK;
+}
+
 }  // extern "C"

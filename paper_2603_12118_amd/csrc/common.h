@@ -56,6 +56,9 @@ struct GemmArgs {
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
 
+// bare MFMA loop (probe.hip): blocks x 8 waves x iters x 32 MFMAs of 32x32x16; out holds blocks*512 floats
+cs_status launch_mfma_loop(float* out, int blocks, int iters, int random_operands, hipStream_t stream);
+
 // ---- attention ------------------------------------------------------------------------------
 struct AttnWork {  // one workgroup: queries [q0,q1) against keys [kv0,kv1), token indices
   int32_t q0, q1, kv0, kv1;

@@ -1,0 +1,82 @@
+"""Micro-benchmarks of the path's kernels on their own, through the C ABI.
+
+    python -m paper_2603_12118_amd.microbench [--json]
+
+* the bare-MFMA ceiling (zero and random operands),
+* every GEMM shape of the 7B-style vision layer and of the merger at M = 8192 / 2048 rows with a plain
+  bf16 store (`cs_linear_bf16`; the fused epilogues are timed in place by `bench.py --breakdown`),
+* `cs_forward_embeddings` at 8, 16 and 32 MB of embedding rows (the tensor sizes for which the paper
+  quotes its forwarding latency, Sec. 4.3).
+
+Attention on its own at segment sizes 64 / 1024 / 8192 is what `bench.py --breakdown` reports as the
+window and full layers of `c2_images` (64, 1024) and the full layers of `c4_video` (8192).
+Inputs are seeded random bf16 values resident in HBM; times are HIP-event means over 20 launches.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+
+GEMM_SHAPES = [  # (name, M, N, K)
+    ("qkv", 8192, 3840, 1280), ("out projection", 8192, 1280, 1280), ("gate|up", 8192, 6912, 1280),
+    ("down", 8192, 1280, 3456), ("merger fc1", 2048, 5120, 5120), ("merger fc2", 2048, 3584, 5120),
+    ("square", 8192, 8192, 8192),
+]
+
+
+def _time(fn, n=20, warm=3):
+    import torch
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n * 1e-3
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--json", action="store_true")
+    args = ap.parse_args()
+    import torch
+    from . import binding as B
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(1)
+    res = {"mfma_ceiling_tflops": {"zero_operands": B.cs_mfma_ceiling(False), "random_operands": B.cs_mfma_ceiling(True)},
+           "gemm": [], "forward_embeddings": []}
+    for name, M, N, K in GEMM_SHAPES:
+        A = torch.randn(M, K, device=dev, generator=g).bfloat16()
+        W = (torch.randn(N, K, device=dev, generator=g) * 0.05).bfloat16()
+        out = torch.empty(M, N, device=dev, dtype=torch.bfloat16)
+        s = _time(lambda: B.cs_linear_bf16(A, W, None, out))
+        res["gemm"].append({"name": name, "M": M, "N": N, "K": K, "us": s * 1e6, "tflops": 2.0 * M * N * K / s / 1e12})
+        del A, W, out
+    hidden = 3584
+    for mb in (8, 16, 32):
+        rows = mb * (1 << 20) // (hidden * 2)
+        src = torch.randn(rows, hidden, device=dev, generator=g).bfloat16()
+        dst = torch.zeros(4 * rows, hidden, device=dev, dtype=torch.bfloat16)
+        idx = (torch.randperm(4 * rows, device=dev, generator=g)[:rows]).to(torch.int64)
+        s = _time(lambda: B.cs_forward_embeddings(src, idx, dst))
+        nbytes = rows * (2 * hidden * 2 + 8)
+        res["forward_embeddings"].append({"MB": mb, "rows": rows, "us": s * 1e6, "GBs": nbytes / s / 1e9})
+        del src, dst, idx
+    if args.json:
+        print(json.dumps(res))
+        return 0
+    c = res["mfma_ceiling_tflops"]
+    print(f"bare MFMA loop: {c['zero_operands']:.0f} TFLOP/s with zero operands, {c['random_operands']:.0f} with random operands")
+    print("| GEMM (plain bf16 store) | M | N | K | us | TFLOP/s |\n|---|---|---|---|---|---|")
+    for r in res["gemm"]:
+        print(f"| {r['name']} | {r['M']} | {r['N']} | {r['K']} | {r['us']:.1f} | {r['tflops']:.0f} |")
+    print("| cs_forward_embeddings | rows | us | GB/s |\n|---|---|---|---|")
+    for r in res["forward_embeddings"]:
+        print(f"| {r['MB']} MB | {r['rows']} | {r['us']:.1f} | {r['GBs']:.0f} |")
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())

@@ -221,3 +221,11 @@ def test_encode_rejects_bad_batches():
                            w.n_items, out.data_ptr(), small.data_ptr(), small.numel(), 0)
     assert st == 3
     torch.cuda.synchronize()
+
+
+def test_mfma_ceiling_probe_reports_a_plausible_rate():
+    """The bare MFMA loop: between a fifth of the nominal bf16 peak and the peak itself, and not
+    faster with random operands (power-limited) than with zeros."""
+    zero = B.cs_mfma_ceiling(False, iters=2000)
+    rnd = B.cs_mfma_ceiling(True, iters=2000)
+    assert 500.0 < rnd <= zero * 1.02 and zero < 2516.6 * 1.02, (zero, rnd)

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(cs_[a-z_0-9]+)\s*\(", hdr))
     assert {"cs_encoder_create", "cs_encode", "cs_forward_embeddings", "cs_encoder_query", "cs_encoder_destroy",
             "cs_plan_tokens", "cs_linear_bf16", "cs_attention_varlen", "cs_status_string", "cs_last_error",
-            "cs_encoder_time_step", "cs_encoder_read_timing"} <= names
+            "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling"} <= names
     lib = C.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
@@ -108,6 +108,13 @@ def test_forward_embeddings_argument_errors_need_no_gpu():
     assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 8, 9) == 1                # bad dtype
     assert B.cs_forward_embeddings_raw(8, 16, 16, 4, 4, 8, B.CS_BF16) == 1         # misaligned src
     assert B.cs_forward_embeddings_raw(0, 0, 0, 0, 4, 8, B.CS_BF16) == 0           # empty: no-op
+
+
+def test_mfma_ceiling_argument_errors_need_no_gpu():
+    out = C.c_double(0.0)
+    assert B.lib().cs_mfma_ceiling(None, 1 << 20, 0, 10, C.byref(out), None) == 1       # no scratch
+    assert B.lib().cs_mfma_ceiling(16, 1024, 0, 10, C.byref(out), None) == 1             # scratch too small
+    assert B.lib().cs_mfma_ceiling(16, 1 << 20, 0, 0, C.byref(out), None) == 1           # no iterations
 
 
 def test_flop_model_matches_hand_count():
