@@ -206,6 +206,24 @@ typedef enum {
 cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
 cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
 
+/* cs_patchify: pixels -> the patch rows cs_encode takes, for callers that hold decoded frames
+ * (the step in front of the encoder task; the paper leaves preprocessing to the model's own
+ * processor, Sec. 3.1).  No resizing: sides must already be multiples of the patch size.
+ *  frames      dev, items back to back, item i = [F_i, 3, H_i, W_i] of in_dtype (CS_F32 or CS_BF16),
+ *              16-byte aligned; every item must start 16-byte aligned (it does when H*W is a multiple of 8)
+ *  frame_dims  HOST int32 [n_items,3] = (F, H, W) in pixels; H, W multiples of patch; F == 1 or a
+ *              multiple of temporal_patch (a single frame is shown temporal_patch times)
+ *  patches     dev [N, 3*temporal_patch*patch*patch] of out_dtype: rows in raster order (t, row, col)
+ *              per item, items in order; inside a row the order is (channel, frame in the temporal
+ *              patch, py, px).  Values are copied (fp32 -> bf16 rounds to nearest even).
+ *  grid_thw    HOST int32 [n_items,3] out, may be NULL: (t, h, w) in patches, as cs_encode takes it
+ *  cu_seqlens  HOST int32 [n_items+1] out, may be NULL
+ * Enqueues one kernel per 32 items on `stream`; allocates nothing.  patch must be even.
+ * Errors (nothing enqueued): CS_ERR_INVALID_ARG, CS_ERR_SHAPE. */
+cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
+                      int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype,
+                      int32_t* grid_thw, int32_t* cu_seqlens, void* stream);
+
 /* Measurement aid: the rate of a bare v_mfma_f32_32x32x16_bf16 loop (no memory traffic) on the
  * current device, the ceiling the GEMMs' roofline fraction is read against.  Runs one warm-up and
  * one timed launch of 256 workgroups x 8 waves x iters x 32 MFMAs on `stream`, waits for it, and

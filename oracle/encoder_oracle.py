@@ -268,6 +268,32 @@ def encode(cfg, W, patches, cu_seqlens, grid_thw) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# pixels -> patch rows (the step in front of the encoder task)
+# --------------------------------------------------------------------------
+def patchify(frames: np.ndarray, temporal_patch: int, patch: int = 14) -> Tuple[np.ndarray, Tuple[int, int, int]]:
+    """frames [F, 3, H, W] of one item -> (patch rows [T*h*w, 3*tp*patch*patch], (T, h, w)).
+
+    Patch (t, r, c) is row (t*h + r)*w + c; inside the row, element
+    ((ch*tp + tt)*patch + py)*patch + px is pixel frames[t*tp + tt, ch, r*patch + py, c*patch + px].
+    An item with a single frame shows that frame in every temporal slot.  Values are copied as they
+    are (no arithmetic); the dtype of `frames` is kept.  Reading: the paper leaves preprocessing to
+    each model's own processor (Sec. 3.1); this is the layout such vision towers take."""
+    F, C, H, W = frames.shape
+    tp = temporal_patch
+    assert C == 3 and H % patch == 0 and W % patch == 0 and (F == 1 or F % tp == 0)
+    T, h, w = (1 if F == 1 else F // tp), H // patch, W // patch
+    out = np.empty((T * h * w, C * tp * patch * patch), frames.dtype)
+    for t in range(T):
+        for r in range(h):
+            for c in range(w):
+                row = out[(t * h + r) * w + c].reshape(C, tp, patch, patch)
+                for tt in range(tp):
+                    f = 0 if F == 1 else t * tp + tt
+                    row[:, tt] = frames[f, :, r * patch:(r + 1) * patch, c * patch:(c + 1) * patch]
+    return out, (T, h, w)
+
+
+# --------------------------------------------------------------------------
 # embedding hand-off
 # --------------------------------------------------------------------------
 def forward_embeddings(src: np.ndarray, placeholder_index: np.ndarray, dst: np.ndarray) -> np.ndarray:

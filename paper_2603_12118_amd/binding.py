@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
         L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
         L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.cs_patchify.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, i32p, i32p, vp]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
         L.cs_encoder_read_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -222,6 +223,24 @@ def cs_attention_varlen(qk, vt, out, seg_cu: Sequence[int], n_heads: int, head_d
     seg = _i32(seg_cu)
     _check(lib().cs_attention_varlen(qk.data_ptr(), vt.data_ptr(), vt.stride(0), out.data_ptr(), _i32p(seg),
                                      len(seg) - 1, n_heads, head_dim, _stream(stream)))
+
+
+def cs_patchify(frames, frame_dims, temporal_patch: int, patch: int = 14, out_dtype=None, stream=None):
+    """frames: device tensor holding the items' [F,3,H,W] pixels back to back (fp32 or bf16);
+    frame_dims: [n_items,3] = (F,H,W).  Returns (patches device tensor, cu_seqlens, grid_thw)."""
+    import torch
+    fd = np.ascontiguousarray(np.asarray(frame_dims, np.int32).reshape(-1, 3))
+    n = fd.shape[0]
+    T = np.where(fd[:, 0] == 1, 1, fd[:, 0] // temporal_patch)
+    rows = int((T * (fd[:, 1] // patch) * (fd[:, 2] // patch)).sum())
+    out_dtype = out_dtype or torch.bfloat16
+    out = torch.empty(rows, 3 * temporal_patch * patch * patch, dtype=out_dtype, device=frames.device)
+    grid = np.zeros((n, 3), np.int32)
+    cu = np.zeros(n + 1, np.int32)
+    dt = {torch.float32: CS_F32, torch.bfloat16: CS_BF16}
+    _check(lib().cs_patchify(frames.data_ptr(), dt[frames.dtype], _i32p(fd), n, temporal_patch, patch, out.data_ptr(),
+                             dt[out_dtype], _i32p(grid), _i32p(cu), _stream(stream)))
+    return out, cu, grid
 
 
 def cs_mfma_ceiling(random_operands: bool, iters: int = 8000, stream=None) -> float:

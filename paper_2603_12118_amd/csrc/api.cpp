@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
+#include <limits>
 #include <map>
 #include <string>
 #include <vector>
@@ -712,6 +714,55 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
   }
   (void)hipFree(dwork);
   return st;
+}
+
+cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
+                      int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype, int32_t* grid_thw,
+                      int32_t* cu_seqlens, void* stream_) {
+  if (!frames || !frame_dims || !patches || n_items <= 0) return fail(CS_ERR_INVALID_ARG, "cs_patchify: NULL argument or no items");
+  if ((in_dtype != CS_F32 && in_dtype != CS_BF16) || (out_dtype != CS_F32 && out_dtype != CS_BF16))
+    return fail(CS_ERR_INVALID_ARG, "cs_patchify: dtype");
+  if (temporal_patch < 1 || patch < 2 || (patch & 1)) return fail(CS_ERR_INVALID_ARG, "cs_patchify: patch sizes");
+  if ((reinterpret_cast<uintptr_t>(frames) | reinterpret_cast<uintptr_t>(patches)) & 15)
+    return fail(CS_ERR_INVALID_ARG, "cs_patchify: frames and patches must be 16-byte aligned");
+  const int64_t in_sz = in_dtype == CS_BF16 ? 2 : 4;
+  const int64_t pdim = 3 * (int64_t)temporal_patch * patch * patch;
+  // validate everything before the first launch
+  int64_t rows = 0;
+  for (int i = 0; i < n_items; ++i) {
+    const int64_t F = frame_dims[3 * i], H = frame_dims[3 * i + 1], W = frame_dims[3 * i + 2];
+    if (F <= 0 || H <= 0 || W <= 0 || H % patch || W % patch || (F != 1 && F % temporal_patch))
+      return fail(CS_ERR_SHAPE, "cs_patchify: item " + std::to_string(i) + ": sides must be multiples of the patch size, "
+                                "frames 1 or a multiple of the temporal patch");
+    if ((F * 3 * H * W * in_sz) % 16) return fail(CS_ERR_SHAPE, "cs_patchify: item " + std::to_string(i) + " does not end 16-byte aligned");
+    rows += (F == 1 ? 1 : F / temporal_patch) * (H / patch) * (W / patch);
+    if (rows > std::numeric_limits<int32_t>::max() / 8) return fail(CS_ERR_SHAPE, "cs_patchify: batch too large");
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  int64_t src_el = 0, dst_el = 0;
+  int32_t cu = 0;
+  if (cu_seqlens) cu_seqlens[0] = 0;
+  for (int i0 = 0; i0 < n_items; i0 += PATCHIFY_ITEMS) {
+    PatchifyItems it = {};
+    it.n = std::min(PATCHIFY_ITEMS, n_items - i0);
+    for (int k = 0; k < it.n; ++k) {
+      const int i = i0 + k;
+      const int32_t F = frame_dims[3 * i], H = frame_dims[3 * i + 1], W = frame_dims[3 * i + 2];
+      const int32_t T = F == 1 ? 1 : F / temporal_patch, h = H / patch, w = W / patch;
+      it.F[k] = F; it.H[k] = H; it.W[k] = W;
+      it.src_off[k] = src_el;
+      it.dst_off[k] = dst_el;
+      it.pair_cu[k + 1] = it.pair_cu[k] + (int64_t)F * 3 * H * (W / 2);
+      src_el += (int64_t)F * 3 * H * W;
+      dst_el += (int64_t)T * h * w * pdim;
+      cu += T * h * w;
+      if (grid_thw) { grid_thw[3 * i] = T; grid_thw[3 * i + 1] = h; grid_thw[3 * i + 2] = w; }
+      if (cu_seqlens) cu_seqlens[i + 1] = cu;
+    }
+    if (cs_status st = launch_patchify(frames, in_dtype == CS_BF16, patches, out_dtype == CS_BF16, it, temporal_patch, patch, stream))
+      return st;
+  }
+  return CS_OK;
 }
 
 cs_status cs_mfma_ceiling(void* scratch, size_t scratch_bytes, int32_t random_operands, int32_t iters, double* tflops,

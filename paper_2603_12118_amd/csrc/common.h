@@ -56,6 +56,18 @@ struct GemmArgs {
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
 
+// pixels -> patch rows (elementwise.hip): up to PATCHIFY_ITEMS items [F,3,H,W] per launch, described by value
+constexpr int PATCHIFY_ITEMS = 32;
+struct PatchifyItems {
+  int32_t n;
+  int32_t F[PATCHIFY_ITEMS], H[PATCHIFY_ITEMS], W[PATCHIFY_ITEMS];
+  int64_t src_off[PATCHIFY_ITEMS];       // first pixel of the item, in elements
+  int64_t dst_off[PATCHIFY_ITEMS];       // first output element of the item
+  int64_t pair_cu[PATCHIFY_ITEMS + 1];   // running count of pixel pairs: item k owns [pair_cu[k], pair_cu[k+1])
+};
+cs_status launch_patchify(const void* frames, int in_bf16, void* out, int out_bf16, const PatchifyItems& items,
+                          int32_t tp, int32_t patch, hipStream_t s);
+
 // bare MFMA loop (probe.hip): blocks x 8 waves x iters x 32 MFMAs of 32x32x16; out holds blocks*512 floats
 cs_status launch_mfma_loop(float* out, int blocks, int iters, int random_operands, hipStream_t stream);
 

@@ -1,5 +1,7 @@
 // Bandwidth-bound kernels: normalisations, input gather/cast, rotary table, position add and the
 // embedding hand-off (row scatter).  All are one pass over HBM with 16-byte (or 8-byte) accesses.
+#include <algorithm>
+
 #include "common.h"
 
 namespace cs {
@@ -274,6 +276,62 @@ cs_status launch_zero_rows(bf16_t* buf, const int32_t* rows, int32_t n_rows, int
   if (cols & 7) return fail(CS_ERR_UNSUPPORTED, "zero_rows: cols must be a multiple of 8");
   const int total = n_rows * (cols >> 3);
   hipLaunchKernelGGL(zero_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, s, buf, rows, n_rows, cols);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- pixels -> patch rows.  One thread per input pixel pair (x, x+1): reads run along image rows,
+// writes are the 14-pixel runs of a patch row.  Output element order inside a patch: (channel,
+// frame inside the temporal patch, py, px); patches in raster order (t, row, col).  An item with a
+// single frame shows it tp times.  Up to PATCHIFY_ITEMS items per launch, described in the
+// kernel arguments (no device-side table to allocate or copy).
+template <bool IN_BF16, bool OUT_BF16>
+__global__ __launch_bounds__(256) void patchify_kernel(const void* __restrict__ frames, void* __restrict__ out,
+                                                       PatchifyItems it, int tp, int patch) {
+  const int pdim = 3 * tp * patch * patch;
+  const int64_t total = it.pair_cu[it.n];
+  for (int64_t gi = (int64_t)blockIdx.x * 256 + threadIdx.x; gi < total; gi += (int64_t)gridDim.x * 256) {
+    int k = 0;
+    while (k + 1 < it.n && gi >= it.pair_cu[k + 1]) ++k;
+    const int F = it.F[k], H = it.H[k], W = it.W[k];
+    const int64_t i = gi - it.pair_cu[k];
+    const int64_t half_w = W >> 1;
+    const int h = H / patch, w = W / patch;
+    const int x = (int)(i % half_w) * 2;
+    int64_t r = i / half_w;
+    const int y = (int)(r % H);
+    r /= H;
+    const int ch = (int)(r % 3), f = (int)(r / 3);
+    float v0, v1;
+    if (IN_BF16) {
+      const uint32_t u = *reinterpret_cast<const uint32_t*>(static_cast<const bf16_t*>(frames) + it.src_off[k] + 2 * i);
+      v0 = __uint_as_float(u << 16);
+      v1 = __uint_as_float(u & 0xFFFF0000u);
+    } else {
+      const float2 u = *reinterpret_cast<const float2*>(static_cast<const float*>(frames) + it.src_off[k] + 2 * i);
+      v0 = u.x;
+      v1 = u.y;
+    }
+    const int row = y / patch, py = y - row * patch, col = x / patch, px = x - col * patch;   // px even: the pair stays in one patch
+    const int t = F == 1 ? 0 : f / tp, tt0 = F == 1 ? 0 : f - t * tp, reps = F == 1 ? tp : 1;
+    for (int rep = 0; rep < reps; ++rep) {
+      const int64_t o = it.dst_off[k] + ((int64_t)(t * h + row) * w + col) * pdim + ((ch * tp + tt0 + rep) * patch + py) * patch + px;
+      if (OUT_BF16) *reinterpret_cast<uint32_t*>(static_cast<bf16_t*>(out) + o) = pack2_e(v0, v1);
+      else *reinterpret_cast<float2*>(static_cast<float*>(out) + o) = make_float2(v0, v1);
+    }
+  }
+}
+
+cs_status launch_patchify(const void* frames, int in_bf16, void* out, int out_bf16, const PatchifyItems& it, int32_t tp,
+                          int32_t patch, hipStream_t s) {
+  if (it.n <= 0 || it.n > PATCHIFY_ITEMS) return fail(CS_ERR_INVALID_ARG, "patchify: 1..32 items per launch");
+  const int64_t total = it.pair_cu[it.n];
+  if (total <= 0) return CS_OK;
+  const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536 * 8);
+  if (in_bf16 && out_bf16) hipLaunchKernelGGL((patchify_kernel<true, true>), dim3(blocks), dim3(256), 0, s, frames, out, it, tp, patch);
+  else if (in_bf16) hipLaunchKernelGGL((patchify_kernel<true, false>), dim3(blocks), dim3(256), 0, s, frames, out, it, tp, patch);
+  else if (out_bf16) hipLaunchKernelGGL((patchify_kernel<false, true>), dim3(blocks), dim3(256), 0, s, frames, out, it, tp, patch);
+  else hipLaunchKernelGGL((patchify_kernel<false, false>), dim3(blocks), dim3(256), 0, s, frames, out, it, tp, patch);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }

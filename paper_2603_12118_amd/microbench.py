@@ -6,7 +6,8 @@
 * every GEMM shape of the 7B-style vision layer and of the merger at M = 8192 / 2048 rows with a plain
   bf16 store (`cs_linear_bf16`; the fused epilogues are timed in place by `bench.py --breakdown`),
 * `cs_forward_embeddings` at 8, 16 and 32 MB of embedding rows (the tensor sizes for which the paper
-  quotes its forwarding latency, Sec. 4.3).
+  quotes its forwarding latency, Sec. 4.3),
+* `cs_patchify` on the eight 448x448 images of the benchmark batch.
 
 Attention on its own at segment sizes 64 / 1024 / 8192 is what `bench.py --breakdown` reports as the
 window and full layers of `c2_images` (64, 1024) and the full layers of `c4_video` (8192).
@@ -64,6 +65,11 @@ def main() -> int:
         nbytes = rows * (2 * hidden * 2 + 8)
         res["forward_embeddings"].append({"MB": mb, "rows": rows, "us": s * 1e6, "GBs": nbytes / s / 1e9})
         del src, dst, idx
+    px = torch.rand(8 * 3 * 448 * 448, device=dev, generator=g)
+    dims = [(1, 448, 448)] * 8
+    s = _time(lambda: B.cs_patchify(px, dims, temporal_patch=2))
+    nbytes = px.numel() * 4 + 8192 * 1176 * 2
+    res["patchify"] = {"workload": "8 x 448x448 fp32 images -> 8192 x 1176 bf16", "us": s * 1e6, "GBs": nbytes / s / 1e9}
     if args.json:
         print(json.dumps(res))
         return 0
@@ -75,6 +81,8 @@ def main() -> int:
     print("| cs_forward_embeddings | rows | us | GB/s |\n|---|---|---|---|")
     for r in res["forward_embeddings"]:
         print(f"| {r['MB']} MB | {r['rows']} | {r['us']:.1f} | {r['GBs']:.0f} |")
+    r = res["patchify"]
+    print(f"cs_patchify, {r['workload']}: {r['us']:.1f} us, {r['GBs']:.0f} GB/s")
     return 0
 
 

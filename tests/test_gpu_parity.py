@@ -229,3 +229,50 @@ def test_mfma_ceiling_probe_reports_a_plausible_rate():
     zero = B.cs_mfma_ceiling(False, iters=2000)
     rnd = B.cs_mfma_ceiling(True, iters=2000)
     assert 500.0 < rnd <= zero * 1.02 and zero < 2516.6 * 1.02, (zero, rnd)
+
+
+# ------------------------------------------------------------------ pixels -> patch rows
+@pytest.mark.parametrize("in_dtype,out_dtype", [(torch.float32, torch.bfloat16), (torch.float32, torch.float32),
+                                                (torch.bfloat16, torch.bfloat16)])
+def test_patchify_is_bit_exact(in_dtype, out_dtype):
+    """Three items back to back (a still image, a non-square image, a 4-frame clip); every output word
+    against the checker's explicit loops on the same stored values."""
+    rng = np.random.default_rng(11)
+    dims = [(1, 28, 42), (1, 56, 28), (4, 28, 28)]
+    frames = [rng.random((F, 3, H, W)).astype(np.float32) for F, H, W in dims]
+    if in_dtype == torch.bfloat16:
+        frames = [wl.round_to_bf16(f) for f in frames]
+    flat = torch.from_numpy(np.concatenate([f.ravel() for f in frames])).to(DEV).to(in_dtype)
+    out, cu, grid = B.cs_patchify(flat, dims, temporal_patch=2, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    ref = [O.patchify(f, 2) for f in frames]
+    assert grid.tolist() == [list(g) for _, g in ref]
+    assert cu.tolist() == np.concatenate([[0], np.cumsum([p.shape[0] for p, _ in ref])]).tolist()
+    want = np.concatenate([p for p, _ in ref])
+    if out_dtype == torch.bfloat16:
+        got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, wl.to_bits_bf16(wl.round_to_bf16(want)))     # fp32 -> bf16: nearest even
+    else:
+        assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_patchify_full_size_batch_and_into_the_encoder():
+    """Eight 448x448 images: patch rows bit-exact against the checker, and the same bits as the
+    benchmark workload's input, so cs_patchify -> cs_encode is the measured path fed from pixels."""
+    w = wl.c2_images(n_layers=1)
+    rng = np.random.default_rng(1)
+    frames = [rng.random((1, 3, 448, 448), dtype=np.float32) for _ in range(8)]          # the workload's own recipe
+    flat = torch.from_numpy(np.concatenate([f.ravel() for f in frames])).to(DEV)
+    out, cu, grid = B.cs_patchify(flat, [(1, 448, 448)] * 8, temporal_patch=2)
+    torch.cuda.synchronize()
+    want = np.concatenate([O.patchify(f, 2)[0] for f in frames])
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, wl.to_bits_bf16(wl.round_to_bf16(want)))
+    assert np.array_equal(cu, w.cu_seqlens) and np.array_equal(grid, w.grid_thw)
+    assert np.array_equal(wl.to_bits_bf16(w.patches), got)
+    enc = B.Encoder(w.cfg, w.weights)
+    a, _ = enc.cs_encode(out, cu, grid)
+    b, _ = enc.cs_encode(torch.from_numpy(wl.to_bits_bf16(w.patches).view(np.int16)).to(DEV).view(torch.bfloat16),
+                         w.cu_seqlens, w.grid_thw)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(cs_[a-z_0-9]+)\s*\(", hdr))
     assert {"cs_encoder_create", "cs_encode", "cs_forward_embeddings", "cs_encoder_query", "cs_encoder_destroy",
             "cs_plan_tokens", "cs_linear_bf16", "cs_attention_varlen", "cs_status_string", "cs_last_error",
-            "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling"} <= names
+            "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling", "cs_patchify"} <= names
     lib = C.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
@@ -108,6 +108,24 @@ def test_forward_embeddings_argument_errors_need_no_gpu():
     assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 8, 9) == 1                # bad dtype
     assert B.cs_forward_embeddings_raw(8, 16, 16, 4, 4, 8, B.CS_BF16) == 1         # misaligned src
     assert B.cs_forward_embeddings_raw(0, 0, 0, 0, 4, 8, B.CS_BF16) == 0           # empty: no-op
+
+
+def test_patchify_argument_errors_need_no_gpu():
+    L = B.lib()
+    i32p = C.POINTER(C.c_int32)
+    def dims(*d):
+        a = np.array(d, np.int32)
+        return a, a.ctypes.data_as(i32p)
+    a, p = dims(1, 30, 28)
+    assert L.cs_patchify(16, B.CS_F32, p, 1, 2, 14, 32, B.CS_BF16, None, None, None) == 2           # side not a multiple of 14
+    a, p = dims(3, 28, 28)
+    assert L.cs_patchify(16, B.CS_F32, p, 1, 2, 14, 32, B.CS_BF16, None, None, None) == 2           # 3 frames, temporal patch 2
+    a, p = dims(1, 28, 28)
+    assert L.cs_patchify(16, 7, p, 1, 2, 14, 32, B.CS_BF16, None, None, None) == 1                  # dtype
+    assert L.cs_patchify(8, B.CS_F32, p, 1, 2, 14, 32, B.CS_BF16, None, None, None) == 1            # misaligned frames
+    assert L.cs_patchify(16, B.CS_F32, p, 1, 2, 13, 32, B.CS_BF16, None, None, None) == 1           # odd patch size
+    assert L.cs_patchify(16, B.CS_F32, p, 0, 2, 14, 32, B.CS_BF16, None, None, None) == 1           # no items
+    assert "cs_patchify" in B.last_error()
 
 
 def test_mfma_ceiling_argument_errors_need_no_gpu():

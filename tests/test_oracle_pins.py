@@ -203,6 +203,36 @@ def test_patchify_element_order_by_hand():
     assert p2[3, 1 * 392 + 1 * 196 + 13 * 14 + 13] == img[0, 1, 27, 27]
 
 
+def test_oracle_patchify_by_hand_brute_force_and_against_the_input_recipe():
+    """oracle.patchify: hand-computed elements, an element-by-element loop written here, and the
+    reshape/transposition the input generator uses (a different construction of the same layout)."""
+    img = np.arange(3 * 28 * 42, dtype=np.float32).reshape(1, 3, 28, 42)
+    p, grid = O.patchify(img, 1)
+    assert grid == (1, 2, 3) and p.shape == (6, 588)
+    assert p[3, 2 * 196 + 3 * 14 + 5] == img[0, 2, 14 + 3, 5]            # patch (r=1,c=0)
+    assert p[5, 0 * 196 + 13 * 14 + 13] == img[0, 0, 27, 41]             # last pixel of channel 0
+    p2, _ = O.patchify(img, 2)                                           # single frame shown twice
+    assert p2[4, 1 * 392 + 0 * 196 + 2 * 14 + 1] == p2[4, 1 * 392 + 1 * 196 + 2 * 14 + 1] == img[0, 1, 16, 15]
+    clip = RNG.random((4, 3, 28, 28)).astype(np.float32)                 # two temporal patches
+    pc, g = O.patchify(clip, 2)
+    assert g == (2, 2, 2)
+    for t in range(2):
+        for r in range(2):
+            for c in range(2):
+                for ch in range(3):
+                    for tt in range(2):
+                        for py in (0, 7, 13):
+                            for px in (0, 6, 13):
+                                assert pc[(t * 2 + r) * 2 + c, ((ch * 2 + tt) * 14 + py) * 14 + px] == \
+                                    clip[2 * t + tt, ch, 14 * r + py, 14 * c + px]
+    for fr, tp in ((img, 1), (img, 2), (clip, 2), (clip, 1)):
+        a, ga = O.patchify(fr, tp)
+        b, gb = wl.patchify(fr, tp)
+        assert ga == gb and np.array_equal(a, b)
+    # every pixel appears exactly once per temporal slot it is shown in
+    assert np.array_equal(np.sort(O.patchify(img, 1)[0].ravel()), np.sort(img.ravel()))
+
+
 def test_duplicated_frame_patch_embed_collapses():
     """With both temporal slots showing the same frame, the 1176-wide patch embedding equals a
     588-wide one whose weight is the sum over the temporal axis."""
