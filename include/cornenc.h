@@ -54,6 +54,11 @@ typedef enum {
 
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
 typedef enum { CS_ARCH_VIT = 0, CS_ARCH_AUDIO = 1 } cs_arch;
+/* Order of an item's patch rows on input.  RASTER: (t, row, col).  MERGE_MAJOR: the order the
+ * stock preprocessors of such vision towers emit, merge group by merge group: (t, row/merge,
+ * col/merge, row%merge, col%merge).  The embedding rows come out in raster order of the merged
+ * grid either way. */
+typedef enum { CS_ORDER_RASTER = 0, CS_ORDER_MERGE_MAJOR = 1 } cs_input_order;
 
 /* Encoder description.  Plain data; set struct_size = sizeof(cs_encoder_config). */
 typedef struct {
@@ -76,6 +81,7 @@ typedef struct {
   float rope_theta;      /* 10000                                                    */
   float norm_eps;        /* 1e-6 (audio 1e-5)                                        */
   int32_t conv_kernel;   /* audio: 3                                                 */
+  int32_t input_order;   /* vit: cs_input_order of the rows of `patches` inside an item */
 } cs_encoder_config;
 
 /* One named weight, HOST memory, element type = config.dtype (bf16 as raw 16-bit words),

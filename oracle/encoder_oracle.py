@@ -293,6 +293,25 @@ def patchify(frames: np.ndarray, temporal_patch: int, patch: int = 14) -> Tuple[
     return out, (T, h, w)
 
 
+def merge_major_order(grid_thw: np.ndarray, merge: int = 2) -> np.ndarray:
+    """Row permutation between the two input orders of a packed batch: entry i is the raster row
+    (t, row, col order inside each item) of the patch that sits at row i when every item is listed
+    merge group by merge group, (t, row/merge, col/merge, row%merge, col%merge), which is how the
+    stock preprocessors of such vision towers emit patches.  raster_patches[perm] is the
+    merge-major batch."""
+    perm = []
+    base = 0
+    for (T, h, w) in np.asarray(grid_thw).tolist():
+        for t in range(T):
+            for R in range(h // merge):
+                for C in range(w // merge):
+                    for dr in range(merge):
+                        for dc in range(merge):
+                            perm.append(base + (t * h + R * merge + dr) * w + C * merge + dc)
+        base += T * h * w
+    return np.asarray(perm, np.int64)
+
+
 # --------------------------------------------------------------------------
 # embedding hand-off
 # --------------------------------------------------------------------------

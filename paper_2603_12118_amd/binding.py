@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcornenc.so")
 
 CS_F32, CS_BF16 = 0, 1
 CS_ARCH_VIT, CS_ARCH_AUDIO = 0, 1
+CS_ORDER_RASTER, CS_ORDER_MERGE_MAJOR = 0, 1
 STEPS = {"front": 1, "norm": 2, "qkv": 3, "attn_window": 4, "attn_full": 5, "proj": 6, "mlp_up": 7, "mlp_down": 8,
          "back": 9}
 
@@ -33,7 +34,7 @@ class cs_encoder_config(C.Structure):
                 ("n_layers", C.c_int32), ("mlp_dim", C.c_int32), ("merge", C.c_int32), ("merger_hidden", C.c_int32),
                 ("out_hidden", C.c_int32), ("window", C.c_int32), ("full_attn_layer_mask", C.c_uint64),
                 ("rope_sections", C.c_int32 * 3), ("rope_theta", C.c_float), ("norm_eps", C.c_float),
-                ("conv_kernel", C.c_int32)]
+                ("conv_kernel", C.c_int32), ("input_order", C.c_int32)]
 
 
 class cs_tensor(C.Structure):
@@ -111,6 +112,7 @@ def make_config(cfg) -> cs_encoder_config:
     c.rope_sections = (C.c_int32 * 3)(*[int(s) for s in cfg.rope_sections])
     c.rope_theta = float(cfg.rope_theta)
     c.norm_eps = float(cfg.norm_eps)
+    c.input_order = {"raster": CS_ORDER_RASTER, "merge_major": CS_ORDER_MERGE_MAJOR}[getattr(cfg, "input_order", "raster")]
     return c
 
 

@@ -102,6 +102,10 @@ namespace cs {
 
 static cs_status check_config(const cs_encoder_config& c) {
   if (c.struct_size != sizeof(cs_encoder_config)) return fail(CS_ERR_INVALID_ARG, "config.struct_size mismatch");
+  if (c.input_order != CS_ORDER_RASTER && c.input_order != CS_ORDER_MERGE_MAJOR)
+    return fail(CS_ERR_INVALID_ARG, "config.input_order");
+  if (c.input_order != CS_ORDER_RASTER && c.arch != CS_ARCH_VIT)
+    return fail(CS_ERR_UNSUPPORTED, "config: input_order applies to vision encoders");
   if (c.arch != CS_ARCH_VIT && c.arch != CS_ARCH_AUDIO) return fail(CS_ERR_INVALID_ARG, "config.arch");
   if ((c.dtype != CS_F32 && c.dtype != CS_BF16) || (c.out_dtype != CS_F32 && c.out_dtype != CS_BF16))
     return fail(CS_ERR_INVALID_ARG, "config.dtype / out_dtype");

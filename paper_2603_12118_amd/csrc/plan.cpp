@@ -76,7 +76,10 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
               for (int dr = 0; dr < mg; ++dr)
                 for (int dc = 0; dc < mg; ++dc) {
                   const int r = R + dr, c = C + dc;
-                  src_row.push_back(cu[i] + (t * h + r) * w + c);
+                  if (cfg.input_order == CS_ORDER_MERGE_MAJOR)
+                    src_row.push_back(cu[i] + (((t * (h / mg) + R / mg) * (w / mg) + C / mg) * mg + dr) * mg + dc);
+                  else
+                    src_row.push_back(cu[i] + (t * h + r) * w + c);
                   pos.push_back(t);
                   pos.push_back(r);
                   pos.push_back(c);

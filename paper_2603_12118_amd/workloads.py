@@ -78,6 +78,7 @@ class EncoderConfig:
     rope_theta: float = 10000.0
     norm_eps: float = 1e-6
     conv_kernel: int = 3         # audio only
+    input_order: str = "raster"  # vit: "raster" or "merge_major" rows inside an item
 
     @property
     def elem_bytes(self) -> int:

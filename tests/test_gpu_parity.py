@@ -276,3 +276,17 @@ def test_patchify_full_size_batch_and_into_the_encoder():
                          w.cu_seqlens, w.grid_thw)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def test_merge_major_input_order_gives_the_same_embeddings():
+    """The same ragged batch handed over merge group by merge group (the checker's permutation applied
+    to the rows): identical bits out, since only the gather at the front of the path changes."""
+    from dataclasses import replace
+    w = wl.small_vit(n_layers=2)
+    perm = O.merge_major_order(w.grid_thw, w.cfg.merge)
+    x = torch.from_numpy(wl.to_bits_bf16(w.patches).view(np.int16)).to(DEV).view(torch.bfloat16)
+    xm = x[torch.from_numpy(perm).to(DEV)].contiguous()
+    a, _ = B.Encoder(w.cfg, w.weights).cs_encode(x, w.cu_seqlens, w.grid_thw)
+    b, _ = B.Encoder(replace(w.cfg, input_order="merge_major"), w.weights).cs_encode(xm, w.cu_seqlens, w.grid_thw)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and not torch.equal(x, xm)

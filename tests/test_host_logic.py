@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
     assert B.lib().cs_status_string(0) == b"ok"
-    assert C.sizeof(B.cs_encoder_config) == 88
+    assert C.sizeof(B.cs_encoder_config) == 96
 
 
 def brute_plan(grid, window, merge=2):
@@ -70,6 +70,23 @@ def test_plan_matches_brute_force_and_checker_geometry(grid):
     # four consecutive internal tokens feed one merged token, in the checker's concat order
     mi = O.merge_index(g, 2)
     assert np.array_equal(src.reshape(-1, 4), mi[out_row])
+
+
+def test_plan_merge_major_input_order():
+    """With merge-major input the planner's source rows are the checker's permutation undone: internal
+    token i reads input row j where perm[j] is the raster row it would read otherwise."""
+    from dataclasses import replace
+    grid = [(1, 18, 34), (3, 10, 12), (1, 2, 2)]
+    g = np.array(grid, np.int32)
+    cu = np.concatenate([[0], np.cumsum(g.prod(1))]).astype(np.int32)
+    src_r, out_r, win_r = B.cs_plan_tokens(wl.vit_7b_config(), cu, g)
+    src_m, out_m, win_m = B.cs_plan_tokens(replace(wl.vit_7b_config(), input_order="merge_major"), cu, g)
+    perm = O.merge_major_order(g, 2)
+    assert np.array_equal(perm[src_m], src_r)
+    assert np.array_equal(out_m, out_r) and np.array_equal(win_m, win_r)
+    bad = replace(wl.audio_config(), input_order="merge_major")
+    with pytest.raises(B.CsError):
+        B.cs_plan_tokens(bad, [0, 16], [[1, 4, 4]])
 
 
 def test_plan_full_attention_config_keeps_merge_groups():

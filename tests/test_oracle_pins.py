@@ -233,6 +233,20 @@ def test_oracle_patchify_by_hand_brute_force_and_against_the_input_recipe():
     assert np.array_equal(np.sort(O.patchify(img, 1)[0].ravel()), np.sort(img.ravel()))
 
 
+def test_merge_major_order_is_the_merge_index_flattened_and_by_hand():
+    g = np.array([[1, 4, 6], [2, 2, 4]])
+    perm = O.merge_major_order(g, 2)
+    assert sorted(perm.tolist()) == list(range(24 + 16))                     # a permutation
+    assert perm[:8].tolist() == [0, 1, 6, 7, 2, 3, 8, 9]                     # first two groups of a 4x6 grid
+    assert perm[24:32].tolist() == [24, 25, 28, 29, 26, 27, 30, 31]          # second item, frame 0
+    # the merged token m of the merger reads exactly the four consecutive merge-major rows 4m..4m+3
+    assert np.array_equal(perm.reshape(-1, 4), O.merge_index(g, 2))
+    # numpy view construction of the same order
+    for (T, h, w), off in ((g[0], 0), (g[1], 24)):
+        idx = np.arange(T * h * w).reshape(T, h // 2, 2, w // 2, 2).transpose(0, 1, 3, 2, 4).ravel() + off
+        assert np.array_equal(perm[off:off + T * h * w], idx)
+
+
 def test_duplicated_frame_patch_embed_collapses():
     """With both temporal slots showing the same frame, the 1176-wide patch embedding equals a
     588-wide one whose weight is the sum over the temporal axis."""
