@@ -82,6 +82,9 @@ typedef struct {
   float norm_eps;        /* 1e-6 (audio 1e-5)                                        */
   int32_t conv_kernel;   /* audio: 3                                                 */
   int32_t input_order;   /* vit: cs_input_order of the rows of `patches` inside an item */
+  int32_t attn_chunk;    /* audio: tokens (frames after the stride-2 convolution) per attention chunk:
+                            attention is block-diagonal over consecutive chunks of a clip, the last one
+                            may be shorter; a multiple of 4; 0: the whole clip (vit: must be 0)   */
 } cs_encoder_config;
 
 /* One named weight, HOST memory, element type = config.dtype (bf16 as raw 16-bit words),

@@ -225,6 +225,18 @@ def sinusoid_positions(length: int, channels: int) -> np.ndarray:
     return np.concatenate([np.sin(a), np.cos(a)], 1)
 
 
+def audio_attention_allowed(clip_tokens: Sequence[int], chunk: int) -> np.ndarray:
+    """Boolean ``[N,N]`` for a batch of clips with the given token counts: a token sees the tokens
+    of its own clip, and with chunk > 0 only those of its own chunk of `chunk` consecutive tokens
+    of that clip (chunks counted from the clip's first token; the last may be shorter)."""
+    item = np.concatenate([np.full(n, i) for i, n in enumerate(clip_tokens)])
+    allowed = item[:, None] == item[None, :]
+    if chunk > 0:
+        local = np.concatenate([np.arange(n) for n in clip_tokens])
+        allowed = allowed & ((local // chunk)[:, None] == (local // chunk)[None, :])
+    return allowed
+
+
 def audio_block(x, W, p, cfg, allowed):
     N = x.shape[0]
     nh, dh, D = cfg.n_heads, cfg.head_dim, cfg.hidden
@@ -242,17 +254,19 @@ def audio_encode(cfg, W: Dict[str, np.ndarray], frames: np.ndarray, cu_seqlens: 
     """The audio encoder task: frame-major log-mel rows ``[sum T_i, n_mels]`` ->
     ``[sum T_i/4, out_hidden]``.  Two k=3 convolutions (stride 1 then 2, padding 1), each
     followed by GELU; sinusoidal positions; pre-LayerNorm blocks with full attention
-    inside a clip; mean over frame pairs; LayerNorm; projection."""
-    xs, item = [], []
+    inside a clip (or, with cfg.attn_chunk > 0, inside each chunk of that many tokens of a clip:
+    the block-diagonal attention long-audio encoders use; the convolutions and positions still
+    run over the whole clip, which is this build's reading); mean over frame pairs; LayerNorm;
+    projection."""
+    xs = []
     for i in range(len(cu_seqlens) - 1):
         mel = np.asarray(frames[cu_seqlens[i]:cu_seqlens[i + 1]], F64).T      # [n_mels, T]
         c1 = gelu(conv1d(mel, W["conv1.weight"], W["conv1.bias"], 1, 1))
         c2 = gelu(conv1d(c1, W["conv2.weight"], W["conv2.bias"], 2, 1))
         xi = c2.T + sinusoid_positions(c2.shape[1], cfg.hidden)
         xs.append(xi)
-        item.append(np.full(xi.shape[0], i))
-    x, item = np.concatenate(xs, 0), np.concatenate(item)
-    allowed = item[:, None] == item[None, :]
+    x = np.concatenate(xs, 0)
+    allowed = audio_attention_allowed([xi.shape[0] for xi in xs], getattr(cfg, "attn_chunk", 0))
     for l in range(cfg.n_layers):
         x = audio_block(x, W, f"blocks.{l}.", cfg, allowed)
     m = cfg.merge

@@ -34,7 +34,7 @@ class cs_encoder_config(C.Structure):
                 ("n_layers", C.c_int32), ("mlp_dim", C.c_int32), ("merge", C.c_int32), ("merger_hidden", C.c_int32),
                 ("out_hidden", C.c_int32), ("window", C.c_int32), ("full_attn_layer_mask", C.c_uint64),
                 ("rope_sections", C.c_int32 * 3), ("rope_theta", C.c_float), ("norm_eps", C.c_float),
-                ("conv_kernel", C.c_int32), ("input_order", C.c_int32)]
+                ("conv_kernel", C.c_int32), ("input_order", C.c_int32), ("attn_chunk", C.c_int32)]
 
 
 class cs_tensor(C.Structure):
@@ -113,6 +113,7 @@ def make_config(cfg) -> cs_encoder_config:
     c.rope_theta = float(cfg.rope_theta)
     c.norm_eps = float(cfg.norm_eps)
     c.input_order = {"raster": CS_ORDER_RASTER, "merge_major": CS_ORDER_MERGE_MAJOR}[getattr(cfg, "input_order", "raster")]
+    c.attn_chunk = int(getattr(cfg, "attn_chunk", 0))
     return c
 
 

@@ -106,6 +106,9 @@ static cs_status check_config(const cs_encoder_config& c) {
     return fail(CS_ERR_INVALID_ARG, "config.input_order");
   if (c.input_order != CS_ORDER_RASTER && c.arch != CS_ARCH_VIT)
     return fail(CS_ERR_UNSUPPORTED, "config: input_order applies to vision encoders");
+  if (c.attn_chunk < 0 || (c.attn_chunk & 3)) return fail(CS_ERR_INVALID_ARG, "config.attn_chunk must be a non-negative multiple of 4");
+  if (c.attn_chunk != 0 && c.arch != CS_ARCH_AUDIO)
+    return fail(CS_ERR_UNSUPPORTED, "config: attn_chunk applies to audio encoders");
   if (c.arch != CS_ARCH_VIT && c.arch != CS_ARCH_AUDIO) return fail(CS_ERR_INVALID_ARG, "config.arch");
   if ((c.dtype != CS_F32 && c.dtype != CS_BF16) || (c.out_dtype != CS_F32 && c.out_dtype != CS_BF16))
     return fail(CS_ERR_INVALID_ARG, "config.dtype / out_dtype");
@@ -623,7 +626,7 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     {
       StepTimer tm(e, full ? CS_STEP_ATTN_FULL : CS_STEP_ATTN_WINDOW, stream);
       if (full) {
-        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = 256; aa.single_tile = 0;
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_full_work); aa.n_work = p.n_full_work; aa.q_per_block = p.full_q_per_block; aa.single_tile = p.full_single_tile;
       } else {
         aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64; aa.single_tile = p.win_single_tile;
       }

@@ -131,6 +131,10 @@ cs_status build_audio_plan(const cs_encoder_config& cfg, const int32_t* cu, cons
   std::vector<int32_t> mel_src(p.n_pad_rows, -1), c1_map(p.n_pad_rows - 2, -1), c2_map(p.n_pad_rows / 2 - 1, -1);
   std::vector<int32_t> zero_rows, pos(p.n_tok), full_work;
   int off = 0, tok = 0;
+  // short chunks: two-wave workgroups of 64 queries instead of eight waves of which most would idle
+  const int qpb = cfg.attn_chunk > 0 && cfg.attn_chunk <= 128 ? 64 : 256;
+  p.full_q_per_block = qpb;
+  p.full_single_tile = cfg.attn_chunk > 0 && cfg.attn_chunk <= 64;
   for (int i = 0; i < n_items; ++i) {
     const int F = grid[3 * i + 2];
     zero_rows.push_back(off);
@@ -143,7 +147,12 @@ cs_status build_audio_plan(const cs_encoder_config& cfg, const int32_t* cu, cons
       c2_map[off / 2 + t] = tok + t;
       pos[tok + t] = t;
     }
-    for (int q = tok; q < tok + F / 2; q += 256) push_work(full_work, q, std::min(q + 256, tok + F / 2), tok, tok + F / 2);
+    // attention segments: the clip, or its chunks of attn_chunk tokens (the last one may be shorter)
+    const int n_tok_i = F / 2, seg = cfg.attn_chunk > 0 ? cfg.attn_chunk : n_tok_i;
+    for (int s0 = 0; s0 < n_tok_i; s0 += seg) {
+      const int s1 = std::min(s0 + seg, n_tok_i);
+      for (int q = s0; q < s1; q += qpb) push_work(full_work, tok + q, tok + std::min(q + qpb, s1), tok + s0, tok + s1);
+    }
     off += F + 2;
     tok += F / 2;
   }

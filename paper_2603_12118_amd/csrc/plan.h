@@ -21,6 +21,8 @@ struct BatchPlan {
   size_t off_full_work = 0; // [n_full_work*4] AttnWork, 256-query blocks of whole items
   int32_t n_win_work = 0, n_full_work = 0;
   bool win_single_tile = false;  // no window has more than 64 tokens
+  int32_t full_q_per_block = 256;   // queries per item of full_work: 256, or 64 when the segments are short chunks
+  bool full_single_tile = false;    // no full_work item has more than 64 keys
   std::vector<int32_t> win_cu;  // host only: window boundaries in internal token order
   // audio
   int64_t n_pad_rows = 0;   // sum(frames_i + 2): rows of the zero-padded frame buffers

@@ -79,6 +79,7 @@ class EncoderConfig:
     norm_eps: float = 1e-6
     conv_kernel: int = 3         # audio only
     input_order: str = "raster"  # vit: "raster" or "merge_major" rows inside an item
+    attn_chunk: int = 0          # audio: tokens per attention chunk (0: whole clip)
 
     @property
     def elem_bytes(self) -> int:

@@ -203,6 +203,21 @@ def test_encode_small_audio():
     check_embeddings(out, ref, "small_audio")
 
 
+@pytest.mark.parametrize("chunk", [8, 52, 100, 160])
+def test_encode_small_audio_chunked_attention(chunk):
+    """Block-diagonal attention over chunks of a clip: one-tile chunks (8, 52), two-tile chunks in
+    64-query workgroups (100), and 256-query workgroups (160); 200 tokens per clip, so the last
+    chunk is shorter in every case."""
+    from dataclasses import replace
+    w = wl.audio_workload("small_audio", replace(wl.audio_config(n_layers=2), attn_chunk=chunk), n_clips=2,
+                          n_frames=400, seq_len=256)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, f"small_audio chunk {chunk}")
+    whole = O.encode(replace(w.cfg, attn_chunk=0), w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    assert np.abs(whole - ref).max() > 1e-3          # the chunking does change the result
+
+
 def test_encode_rejects_bad_batches():
     w = wl.small_vit(n_layers=1, full_layers=())
     enc = B.Encoder(w.cfg, w.weights)

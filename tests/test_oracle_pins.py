@@ -247,6 +247,27 @@ def test_merge_major_order_is_the_merge_index_flattened_and_by_hand():
         assert np.array_equal(perm[off:off + T * h * w], idx)
 
 
+def test_audio_chunk_mask_by_loops_and_per_chunk_sdpa():
+    """Chunked audio attention: the mask against a double loop written here, its class sizes by hand,
+    and attention under it against PyTorch SDPA run chunk by chunk."""
+    lens, chunk = [20, 12], 8
+    m = O.audio_attention_allowed(lens, chunk)
+    starts = [0, 20]
+    for p in range(32):
+        for q in range(32):
+            ip, iq = int(p >= 20), int(q >= 20)
+            want = ip == iq and (p - starts[ip]) // chunk == (q - starts[iq]) // chunk
+            assert m[p, q] == want
+    assert m.sum(1).tolist() == [8] * 16 + [4] * 4 + [8] * 8 + [4] * 4       # chunks 8,8,4 | 8,4
+    assert np.array_equal(O.audio_attention_allowed(lens, 0), O.audio_attention_allowed(lens, 64))
+    q, k, v = (RNG.standard_normal((32, 3, 16)) for _ in range(3))
+    mine = O.attention(q, k, v, m)
+    for a, b in ((0, 8), (8, 16), (16, 20), (20, 28), (28, 32)):
+        ref = F.scaled_dot_product_attention(T64(q[a:b]).transpose(0, 1), T64(k[a:b]).transpose(0, 1),
+                                             T64(v[a:b]).transpose(0, 1)).transpose(0, 1)
+        assert np.allclose(mine[a:b], ref.numpy(), atol=1e-12)
+
+
 def test_duplicated_frame_patch_embed_collapses():
     """With both temporal slots showing the same frame, the 1176-wide patch embedding equals a
     588-wide one whose weight is the sum over the temporal axis."""
