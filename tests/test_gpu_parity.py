@@ -96,7 +96,9 @@ def test_forward_embeddings_workload_spans():
 
 
 # ------------------------------------------------------------------ contraction kernels on their own
-@pytest.mark.parametrize("M,N,K", [(300, 200, 128), (1000, 520, 1216), (257, 3840, 1280), (2048, 1280, 3456)])
+# one K slice; one row; N a multiple of 4 only; ragged tails of every tile shape; the layer shapes
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (1, 8, 64), (100, 36, 192), (300, 200, 128), (1000, 520, 1216),
+                                   (257, 3840, 1280), (2048, 1280, 3456), (3000, 1280, 256)])
 def test_linear_matches_oracle(M, N, K):
     rng = np.random.default_rng(M + N)
     A = wl.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
@@ -186,6 +188,17 @@ def test_encode_small_ragged_vit(sections):
     torch.cuda.synchronize()
     a = int(w.out_rows[0])
     assert (o1 - out[a:a + int(w.out_rows[1])]).abs().max().item() <= 1e-2
+
+
+def test_encode_smallest_items():
+    """The degenerate sizes: a single 2x2-patch image (one embedding row), and a batch that mixes it
+    with a one-window image and a one-merge-row strip."""
+    for sizes in ([(28, 28)], [(28, 28), (112, 112), (28, 224)]):
+        w = wl.small_vit(sizes_px=tuple(sizes), n_layers=2)
+        ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+        enc, out = run_encode(w)
+        assert out.shape[0] == sum((a // 28) * (b // 28) for a, b in sizes)
+        check_embeddings(out, ref, f"tiny items {sizes}")
 
 
 def test_encode_video_clip_small():
