@@ -107,7 +107,10 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     dominant = "mlp_up"
+    # every 8th launch of the dominant kernel is bracketed by a HIP event pair (4 per step): an event
+    # pair idles the stream for about 5 us on either side of the launch, 0.36 ms per step if all 32 are timed
     enc.cs_encoder_time_step(B.STEPS[dominant])
+    enc.cs_encoder_time_every(8)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for _ in range(args.steps):
@@ -116,6 +119,7 @@ def main() -> int:
     dt = time.perf_counter() - t1
     dom_ms, dom_n = enc.cs_encoder_read_timing()
     enc.cs_encoder_time_step(0)
+    enc.cs_encoder_time_every(1)
 
     fl = algorithmic_flops(w.cfg, w.grid_thw)
     n_in = int(w.cu_seqlens[-1])

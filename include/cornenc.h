@@ -213,6 +213,10 @@ typedef enum {
   CS_STEP_BACK = 9         /* final norm, merger / pooling, output projection       */
 } cs_step;
 cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
+/* An event pair costs the stream about 5 us of idle time on either side of the launch it brackets
+ * (measured: 0.36 ms per step when all 32 launches of one step are timed).  cs_encoder_time_every(enc, n)
+ * times only every n-th launch of the selected step (n >= 1; default 1), counted from the call. */
+cs_status cs_encoder_time_every(cs_encoder* enc, int32_t every);
 cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
 
 /* cs_patchify: pixels -> the patch rows cs_encode takes, for callers that hold decoded frames

@@ -64,12 +64,14 @@ def lib() -> C.CDLL:
         L.cs_patchify.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, i32p, i32p, vp]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
+        L.cs_encoder_time_every.argtypes = [vp, C.c_int32]
         L.cs_encoder_read_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         L.cs_status_string.argtypes = [C.c_int]
         L.cs_status_string.restype = C.c_char_p
         L.cs_last_error.restype = C.c_char_p
         for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
-                  "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_read_timing"):
+                  "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
+                  "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -156,6 +158,9 @@ class Encoder:
 
     def cs_encoder_time_step(self, step: int) -> None:
         _check(lib().cs_encoder_time_step(self._h, step))
+
+    def cs_encoder_time_every(self, every: int) -> None:
+        _check(lib().cs_encoder_time_every(self._h, every))
 
     def cs_encoder_read_timing(self):
         ms, n = C.c_double(), C.c_int64()

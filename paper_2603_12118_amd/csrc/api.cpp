@@ -91,6 +91,8 @@ struct cs_encoder {
   int stage_next = 0;
   // optional per-step event timing
   int time_step = 0;
+  int time_every = 1;                // of the launches of time_step, every time_every-th is timed
+  int64_t time_seen = 0;
   std::vector<hipEvent_t> ev_pool;   // pairs: start, stop
   size_t ev_used = 0;
 
@@ -377,6 +379,7 @@ struct StepTimer {
   hipStream_t stream;
   bool on;
   StepTimer(cs_encoder* enc, int step, hipStream_t s) : e(enc), stream(s), on(enc->time_step == step) {
+    if (on) on = (e->time_seen++ % e->time_every) == 0;
     if (!on) return;
     if (e->ev_used + 2 > e->ev_pool.size()) {
       hipEvent_t a = nullptr, b = nullptr;
@@ -480,6 +483,14 @@ void cs_encoder_destroy(cs_encoder* e) {
 cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step) {
   if (!enc || step < CS_STEP_NONE || step > CS_STEP_BACK) return fail(CS_ERR_INVALID_ARG, "cs_encoder_time_step");
   enc->time_step = step;
+  enc->time_seen = 0;
+  return CS_OK;
+}
+
+cs_status cs_encoder_time_every(cs_encoder* enc, int32_t every) {
+  if (!enc || every < 1) return fail(CS_ERR_INVALID_ARG, "cs_encoder_time_every");
+  enc->time_every = every;
+  enc->time_seen = 0;
   return CS_OK;
 }
 
