@@ -219,6 +219,25 @@ cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
 cs_status cs_encoder_time_every(cs_encoder* enc, int32_t every);
 cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
 
+/* cs_pack_batch: host-only choice of the items that go into the next packed cs_encode call of an
+ * encoder shared by several apps (Sec. 3.1 "Component Sharing": equivalent encoder tasks share one
+ * executor, so items of different requests and models queue at the same encoder).  The paper
+ * names no policy; this one is first-fit in arrival order under a row budget:
+ *   - pending items are given oldest first, item i with rows_i = t*h*w input rows (grid_thw as
+ *     cs_encode takes it);
+ *   - the oldest item is always taken, even when it alone exceeds the budget (nothing starves);
+ *   - every further item, in order, is taken if it still fits (sum of rows <= row_budget) and
+ *     fewer than max_items are taken; items that do not fit are skipped, later smaller ones may
+ *     still be taken.
+ *  selected    HOST int32 out [n_pending]: indices of the taken items, increasing
+ *  n_selected  HOST out
+ *  cu_seqlens  HOST int32 out [n_taken+1], may be NULL; packed_grid HOST int32 out [n_taken,3], may be
+ *              NULL: the arguments of the cs_encode call over the taken items in that order
+ * Errors: CS_ERR_INVALID_ARG (NULL, n_pending <= 0, max_items <= 0, row_budget <= 0), CS_ERR_SHAPE
+ * (an item with a non-positive dimension, or more than 2^28 rows in the batch). */
+cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_budget, int32_t max_items,
+                        int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid);
+
 /* cs_patchify: pixels -> the patch rows cs_encode takes, for callers that hold decoded frames
  * (the step in front of the encoder task; the paper leaves preprocessing to the model's own
  * processor, Sec. 3.1).  No resizing: sides must already be multiples of the patch size.

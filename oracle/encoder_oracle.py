@@ -327,6 +327,25 @@ def merge_major_order(grid_thw: np.ndarray, merge: int = 2) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# which pending items share the next packed call
+# --------------------------------------------------------------------------
+def pack_batch(rows: Sequence[int], row_budget: int, max_items: int) -> list:
+    """First-fit in arrival order: `rows` lists the pending items' input-row counts oldest first.
+    The oldest item is always taken; every later one is taken when the total stays within the
+    budget and fewer than max_items are taken.  Returns the taken indices.  (The paper shares one
+    encoder between apps, Sec. 3.1 "Component Sharing", and names no batching policy; this is the
+    policy this build documents.)"""
+    taken, total = [], 0
+    for i, r in enumerate(rows):
+        if len(taken) >= max_items:
+            break
+        if not taken or total + r <= row_budget:
+            taken.append(i)
+            total += r
+    return taken
+
+
+# --------------------------------------------------------------------------
 # embedding hand-off
 # --------------------------------------------------------------------------
 def forward_embeddings(src: np.ndarray, placeholder_index: np.ndarray, dst: np.ndarray) -> np.ndarray:

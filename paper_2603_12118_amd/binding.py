@@ -61,6 +61,7 @@ def lib() -> C.CDLL:
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
         L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
         L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.cs_pack_batch.argtypes = [i32p, C.c_int32, i64, C.c_int32, i32p, i32p, i32p, i32p]
         L.cs_patchify.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, i32p, i32p, vp]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
@@ -71,7 +72,7 @@ def lib() -> C.CDLL:
         L.cs_last_error.restype = C.c_char_p
         for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
-                  "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling"):
+                  "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -231,6 +232,20 @@ def cs_attention_varlen(qk, vt, out, seg_cu: Sequence[int], n_heads: int, head_d
     seg = _i32(seg_cu)
     _check(lib().cs_attention_varlen(qk.data_ptr(), vt.data_ptr(), vt.stride(0), out.data_ptr(), _i32p(seg),
                                      len(seg) - 1, n_heads, head_dim, _stream(stream)))
+
+
+def cs_pack_batch(grid_thw, row_budget: int, max_items: int = 1 << 30):
+    """First-fit choice of pending items (oldest first) for the next packed call.
+    Returns (selected indices, cu_seqlens, packed grid_thw)."""
+    g = np.ascontiguousarray(np.asarray(grid_thw, np.int32).reshape(-1, 3))
+    n = g.shape[0]
+    sel = np.zeros(max(n, 1), np.int32)
+    cu = np.zeros(n + 1, np.int32)
+    pg = np.zeros((max(n, 1), 3), np.int32)
+    k = C.c_int32(0)
+    _check(lib().cs_pack_batch(_i32p(g), n, int(row_budget), int(min(max_items, 1 << 30)), _i32p(sel), C.byref(k),
+                               _i32p(cu), _i32p(pg)))
+    return sel[:k.value].copy(), cu[:k.value + 1].copy(), pg[:k.value].copy()
 
 
 def cs_patchify(frames, frame_dims, temporal_patch: int, patch: int = 14, out_dtype=None, stream=None):

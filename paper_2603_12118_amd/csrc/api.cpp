@@ -734,6 +734,32 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
   return st;
 }
 
+cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_budget, int32_t max_items,
+                        int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid) {
+  if (!grid_thw || !selected || !n_selected || n_pending <= 0 || max_items <= 0 || row_budget <= 0)
+    return fail(CS_ERR_INVALID_ARG, "cs_pack_batch: NULL argument or non-positive count / budget");
+  for (int i = 0; i < n_pending; ++i) {
+    const int64_t t = grid_thw[3 * i], h = grid_thw[3 * i + 1], w = grid_thw[3 * i + 2];
+    if (t <= 0 || h <= 0 || w <= 0 || t * h * w > (int64_t)1 << 28)
+      return fail(CS_ERR_SHAPE, "cs_pack_batch: item " + std::to_string(i) + " has a non-positive or oversized grid");
+  }
+  int64_t rows = 0;
+  int32_t taken = 0;
+  if (cu_seqlens) cu_seqlens[0] = 0;
+  for (int i = 0; i < n_pending && taken < max_items; ++i) {
+    const int64_t r = (int64_t)grid_thw[3 * i] * grid_thw[3 * i + 1] * grid_thw[3 * i + 2];
+    if (taken > 0 && rows + r > row_budget) continue;
+    if (rows + r > (int64_t)1 << 28) return fail(CS_ERR_SHAPE, "cs_pack_batch: batch too large");
+    rows += r;
+    selected[taken] = i;
+    if (packed_grid) for (int k = 0; k < 3; ++k) packed_grid[3 * taken + k] = grid_thw[3 * i + k];
+    if (cu_seqlens) cu_seqlens[taken + 1] = (int32_t)rows;
+    ++taken;
+  }
+  *n_selected = taken;
+  return CS_OK;
+}
+
 cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
                       int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype, int32_t* grid_thw,
                       int32_t* cu_seqlens, void* stream_) {

@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(cs_[a-z_0-9]+)\s*\(", hdr))
     assert {"cs_encoder_create", "cs_encode", "cs_forward_embeddings", "cs_encoder_query", "cs_encoder_destroy",
             "cs_plan_tokens", "cs_linear_bf16", "cs_attention_varlen", "cs_status_string", "cs_last_error",
-            "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling", "cs_patchify"} <= names
+            "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling", "cs_patchify", "cs_pack_batch",
+            "cs_encoder_time_every"} <= names
     lib = C.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
@@ -125,6 +126,24 @@ def test_forward_embeddings_argument_errors_need_no_gpu():
     assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 8, 9) == 1                # bad dtype
     assert B.cs_forward_embeddings_raw(8, 16, 16, 4, 4, 8, B.CS_BF16) == 1         # misaligned src
     assert B.cs_forward_embeddings_raw(0, 0, 0, 0, 4, 8, B.CS_BF16) == 0           # empty: no-op
+
+
+def test_pack_batch_matches_the_checker_and_feeds_the_planner():
+    rng = np.random.default_rng(9)
+    for _ in range(100):
+        n = int(rng.integers(1, 10))
+        grid = np.stack([rng.integers(1, 3, n), 2 * rng.integers(1, 12, n), 2 * rng.integers(1, 12, n)], 1).astype(np.int32)
+        rows = grid.prod(1).tolist()
+        budget, cap = int(rng.integers(1, 600)), int(rng.integers(1, 6))
+        sel, cu, pg = B.cs_pack_batch(grid, budget, cap)
+        assert sel.tolist() == O.pack_batch(rows, budget, cap)
+        assert np.array_equal(pg, grid[sel]) and cu.tolist() == [0] + np.cumsum(grid[sel].prod(1)).tolist()
+        src, out_row, win_cu = B.cs_plan_tokens(wl.vit_7b_config(), cu, pg)          # a batch cs_encode accepts
+        assert len(src) == cu[-1]
+    with pytest.raises(B.CsError):
+        B.cs_pack_batch([[1, 0, 4]], 100)
+    with pytest.raises(B.CsError):
+        B.cs_pack_batch([[1, 4, 4]], 0)
 
 
 def test_patchify_argument_errors_need_no_gpu():

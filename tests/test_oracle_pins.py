@@ -268,6 +268,26 @@ def test_audio_chunk_mask_by_loops_and_per_chunk_sdpa():
         assert np.allclose(mine[a:b], ref.numpy(), atol=1e-12)
 
 
+def test_pack_batch_by_hand_and_by_its_defining_properties():
+    assert O.pack_batch([100, 900, 50, 60, 10], 200, 10) == [0, 2, 4]        # 900 and then 60 do not fit
+    assert O.pack_batch([500, 10], 200, 10) == [0]                           # oldest alone over budget; 10 would exceed it further
+    assert O.pack_batch([10, 10, 10, 10], 1000, 2) == [0, 1]                 # item limit
+    assert O.pack_batch([200], 200, 1) == [0]
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        rows = rng.integers(1, 400, size=rng.integers(1, 12)).tolist()
+        budget, cap = int(rng.integers(1, 900)), int(rng.integers(1, 8))
+        sel = O.pack_batch(rows, budget, cap)
+        assert sel[0] == 0 and sel == sorted(set(sel)) and len(sel) <= cap
+        tot = 0
+        for i in range(len(rows)):                     # replay: an item is left out only if it did not fit then, or the cap was reached
+            if i in sel:
+                tot += rows[i]
+                assert i == 0 or tot <= budget
+            elif sum(1 for j in sel if j < i) < cap:
+                assert tot + rows[i] > budget
+
+
 def test_duplicated_frame_patch_embed_collapses():
     """With both temporal slots showing the same frame, the 1176-wide patch embedding equals a
     588-wide one whose weight is the sum over the temporal axis."""
