@@ -73,6 +73,21 @@ def test_plan_matches_brute_force_and_checker_geometry(grid):
     assert np.array_equal(src.reshape(-1, 4), mi[out_row])
 
 
+def test_plan_random_batches_against_brute_force():
+    """Sixty seeded random batches (1-5 items, 1-3 frames, even sides up to 44, window 4 or 8)."""
+    from dataclasses import replace
+    rng = np.random.default_rng(17)
+    for _ in range(60):
+        n = int(rng.integers(1, 6))
+        grid = [(int(rng.integers(1, 4)), 2 * int(rng.integers(1, 23)), 2 * int(rng.integers(1, 23))) for _ in range(n)]
+        win = int(rng.choice([4, 8]))
+        g = np.array(grid, np.int32)
+        cu = np.concatenate([[0], np.cumsum(g.prod(1))]).astype(np.int32)
+        src, out_row, win_cu = B.cs_plan_tokens(replace(wl.vit_7b_config(), window=win), cu, g)
+        bs, bo, bw = brute_plan(grid, win)
+        assert np.array_equal(src, bs) and np.array_equal(out_row, bo) and np.array_equal(win_cu, bw), (grid, win)
+
+
 def test_plan_merge_major_input_order():
     """With merge-major input the planner's source rows are the checker's permutation undone: internal
     token i reads input row j where perm[j] is the raster row it would read otherwise."""
