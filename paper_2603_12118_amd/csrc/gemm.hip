@@ -334,8 +334,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // paid once per chunk (the stores in between keep the compiler from hoisting the loads).  With
   // four waves per workgroup (one per SIMD, or small tiles) the registers for the whole wave tile
   // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
+  // With eight waves there is room for one row block only: it is fetched before the last K slice,
+  // and each chunk's registers are refilled for the next row block as soon as the chunk is stored.
   constexpr bool HOLD = EPI == EPI_RESADD_F32 && NWAVES <= 4;
-  [[maybe_unused]] f32x4 held[HOLD ? TM : 1][HOLD ? TN : 1][4];
+  constexpr bool HOLD_ROW = EPI == EPI_RESADD_F32 && NWAVES > 4;
+  [[maybe_unused]] f32x4 held[HOLD ? TM : 1][(HOLD || HOLD_ROW) ? TN : 1][4];
+  [[maybe_unused]] auto fetch_old = [&](int i, int j, f32x4 (&dst)[4]) {
+    const int r = lane >> 3, c = (lane & 7) * 4;
+    int n = n0 + wn * WN + j * 32 + c;
+    n = n < N ? n : N - 4;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      int m = m0 + wm * WM + i * 32 + it * 8 + r;
+      m = m < M ? m : M - 1;
+      int64_t row = m;
+      if (g.row_map) {
+        row = g.row_map[m];
+        row = row < 0 ? 0 : row;
+      }
+      dst[it] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.out) + row * g.ldo + n);
+    }
+  };
   // The bias of the lane's columns is fetched there too (a load inside the epilogue waits out its
   // latency once per chunk).
   f32x4 bias_r[TN][4];
@@ -349,25 +368,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         if (g.bias && n < N) bias_r[j][q] = *reinterpret_cast<const f32x4*>(g.bias + n);
       }
     if constexpr (HOLD) {
-      const int r = lane >> 3, c = (lane & 7) * 4;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-          int m = m0 + wm * WM + i * 32 + it * 8 + r;
-          m = m < M ? m : M - 1;
-          int64_t row = m;
-          if (g.row_map) {
-            row = g.row_map[m];
-            row = row < 0 ? 0 : row;
-          }
+        for (int j = 0; j < TN; ++j) fetch_old(i, j, held[i][j]);
+    } else if constexpr (HOLD_ROW) {
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            int n = n0 + wn * WN + j * 32 + c;
-            n = n < N ? n : N - 4;
-            held[i][j][it] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.out) + row * g.ldo + n);
-          }
-        }
+      for (int j = 0; j < TN; ++j) fetch_old(0, j, held[0][j]);
     }
   });
 
@@ -475,7 +482,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         const int col0 = nw + j0 * 32;
         if constexpr (EPI == EPI_RESADD_F32) {
           store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true,
-                                       HOLD ? held[i][j0] : nullptr);
+                                       HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
+          if constexpr (HOLD_ROW) {
+            if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
+          }
         } else if constexpr (OUT_F32) {
           store_block<NB, float, false>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true);
         } else if constexpr (EPI == EPI_QKV) {
