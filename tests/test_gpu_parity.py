@@ -201,6 +201,19 @@ def test_encode_smallest_items():
         check_embeddings(out, ref, f"tiny items {sizes}")
 
 
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_encode_random_small_batches(seed):
+    """Seeded random batches of 1-4 images with sides of 2..12 patches (even), one window layer and
+    one full layer: ragged windows of every size, items smaller than a window, mixed into one call."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 5))
+    sizes = tuple((28 * int(rng.integers(1, 7)), 28 * int(rng.integers(1, 7))) for _ in range(n))
+    w = wl.small_vit(sizes_px=sizes, n_layers=2)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, f"random batch {sizes}")
+
+
 def test_encode_video_clip_small():
     cfg = wl.vit_7b_config(2, rope_sections=(8, 16, 16))
     w = wl.video_workload("small_video", replace(cfg, full_attn_layers=(1,)), 1, 6, (140, 196), seq_len=512)
