@@ -214,6 +214,16 @@ def test_encode_random_small_batches(seed):
     check_embeddings(out, ref, f"random batch {sizes}")
 
 
+@pytest.mark.parametrize("window", [4, 16])
+def test_encode_other_window_sizes(window):
+    """Windows of 16 tokens, and of up to 256 tokens (four key tiles per 64-query work item)."""
+    w = wl.small_vit(sizes_px=((252, 476), (84, 140)), n_layers=2)
+    w = replace(w, cfg=replace(w.cfg, window=window))
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    check_embeddings(out, ref, f"window {window}")
+
+
 def test_encode_video_clip_small():
     cfg = wl.vit_7b_config(2, rope_sections=(8, 16, 16))
     w = wl.video_workload("small_video", replace(cfg, full_attn_layers=(1,)), 1, 6, (140, 196), seq_len=512)
