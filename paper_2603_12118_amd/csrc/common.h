@@ -56,6 +56,24 @@ struct GemmArgs {
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
 
+// ---- write-through global stores -----------------------------------------------------------
+// Every XCD has its own L2, and the end of a kernel writes back whatever is dirty in it before the
+// next kernel may read it from another XCD.  With plain stores that write-back (up to 4 MB per
+// XCD) sits at the end of every kernel; stores of agent scope (sc1) go through the L2 as they are
+// issued and leave it clean.  Measured: gate|up GEMM 153 -> 145 us, QKV GEMM -3.5 %, the kernels
+// that read the data next unchanged.
+typedef float wt_f32x4 __attribute__((ext_vector_type(4)));
+typedef float wt_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_wt16(void* p, wt_f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_wt8(void* p, wt_f32x2 v) {
+  asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_wt4(void* p, float v) {
+  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // pixels -> patch rows (elementwise.hip): up to PATCHIFY_ITEMS items [F,3,H,W] per launch, described by value
 constexpr int PATCHIFY_ITEMS = 32;
 struct PatchifyItems {

@@ -75,15 +75,15 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
       pk.x = pack2_e(o0, o1);
       pk.y = pack2_e(o2, o3);
       if (split_group == 0) {
-        reinterpret_cast<uint2*>(y + row * dim)[c] = pk;
+        store_wt8(reinterpret_cast<uint2*>(y + row * dim) + c, __builtin_bit_cast(wt_f32x2, pk));
       } else {
         // hi | lo halves of a row of `split_group` tokens: lo = value - hi, again rounded to bf16
         bf16_t* dst = y + (row / split_group) * (2 * split_group * dim) + (row % split_group) * dim;
-        reinterpret_cast<uint2*>(dst)[c] = pk;
+        store_wt8(reinterpret_cast<uint2*>(dst) + c, __builtin_bit_cast(wt_f32x2, pk));
         uint2 lo;
         lo.x = pack2_e(o0 - __uint_as_float(pk.x << 16), o1 - __uint_as_float(pk.x & 0xFFFF0000u));
         lo.y = pack2_e(o2 - __uint_as_float(pk.y << 16), o3 - __uint_as_float(pk.y & 0xFFFF0000u));
-        reinterpret_cast<uint2*>(dst + split_group * dim)[c] = lo;
+        store_wt8(reinterpret_cast<uint2*>(dst + split_group * dim) + c, __builtin_bit_cast(wt_f32x2, lo));
       }
     }
   }
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void gather_cast_kernel(const void* __restrict
         pk.y = pack2_e(v.z, v.w);
       }
     }
-    *reinterpret_cast<uint2*>(dst + r * dst_cols + c) = pk;
+    store_wt8(dst + r * dst_cols + c, __builtin_bit_cast(wt_f32x2, pk));
   }
 }
 
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restri
       if (err_flag && c == 0) *err_flag = 1;
       continue;
     }
-    dst[d * chunks_per_row + c] = src[t];
+    store_wt16(dst + d * chunks_per_row + c, __builtin_bit_cast(wt_f32x4, src[t]));
   }
 }
 

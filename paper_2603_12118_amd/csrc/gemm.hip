@@ -102,10 +102,10 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
     if constexpr (ES == 4) {
       f32x4* d4 = reinterpret_cast<f32x4*>(dst);
       if constexpr (ACCUM) *d4 = (held ? held[it] : *d4) + piece;
-      else *d4 = piece;
+      else store_wt16(d4, piece);
     } else {
       if (wide && n + 8 <= col_end) {
-        *reinterpret_cast<f32x4*>(dst) = piece;
+        store_wt16(dst, piece);
       } else {
         const f32x2 lo = {piece[0], piece[1]}, hi = {piece[2], piece[3]};
         *reinterpret_cast<f32x2*>(dst) = lo;
