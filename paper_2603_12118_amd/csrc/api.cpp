@@ -358,7 +358,7 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   w.xn = take((size_t)N * D * 4);            // bf16 tokens; twice that for the merger's hi|lo input
   w.attn = take((size_t)N * D * 2);
   w.qk = take((size_t)N * 2 * D * 2);
-  w.ld_vt = round_up(N, 8);
+  w.ld_vt = round_up(N, 64);   // rows of v^T start on 128-byte lines (write-through stores need that)
   w.vt = take((size_t)D * w.ld_vt * 2);
   size_t big = (size_t)N * e->I_pad * 2;                                   // MLP activation
   if (c.arch == CS_ARCH_VIT) {

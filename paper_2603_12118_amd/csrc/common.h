@@ -62,6 +62,11 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
 // XCD) sits at the end of every kernel; stores of agent scope (sc1) go through the L2 as they are
 // issued and leave it clean.  Measured: gate|up GEMM 153 -> 145 us, QKV GEMM -3.5 %, the kernels
 // that read the data next unchanged.
+// ONLY for 128-byte lines that a single workgroup (or workgroups of one XCD) writes completely:
+// a line written in parts from two XCDs came out with stale bytes (seen with head rows of 160
+// bytes written by one workgroup per head), and small strided pieces lose the L2's write
+// combining (8-byte pieces of 32 rows per instruction: 50 % slower).  Callers pass `wt` = the
+// destination's base and row pitch are multiples of 128 bytes and so is every workgroup's extent.
 typedef float wt_f32x4 __attribute__((ext_vector_type(4)));
 typedef float wt_f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void store_wt16(void* p, wt_f32x4 v) {
@@ -70,8 +75,16 @@ __device__ __forceinline__ void store_wt16(void* p, wt_f32x4 v) {
 __device__ __forceinline__ void store_wt8(void* p, wt_f32x2 v) {
   asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ void store_wt4(void* p, float v) {
-  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+__device__ __forceinline__ void store16(void* p, wt_f32x4 v, bool wt) {
+  if (wt) store_wt16(p, v);
+  else *static_cast<wt_f32x4*>(p) = v;
+}
+__device__ __forceinline__ void store8(void* p, wt_f32x2 v, bool wt) {
+  if (wt) store_wt8(p, v);
+  else *static_cast<wt_f32x2*>(p) = v;
+}
+__host__ __device__ inline bool lines_exclusive(const void* base, int64_t pitch_bytes) {
+  return ((reinterpret_cast<uintptr_t>(base) | static_cast<uintptr_t>(pitch_bytes)) & 127) == 0;
 }
 
 // pixels -> patch rows (elementwise.hip): up to PATCHIFY_ITEMS items [F,3,H,W] per launch, described by value

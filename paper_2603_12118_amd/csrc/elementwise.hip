@@ -25,7 +25,8 @@ constexpr int NORM_MAX_V4 = 8;  // a wave keeps a row of up to 64*4*8 = 2048 flo
 template <int MODE>
 __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                    const float* __restrict__ bias, float eps,
-                                                   bf16_t* __restrict__ y, int64_t rows, int dim, int pool, int split_group) {
+                                                   bf16_t* __restrict__ y, int64_t rows, int dim, int pool, int split_group,
+                                                   bool wt) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -75,15 +76,15 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
       pk.x = pack2_e(o0, o1);
       pk.y = pack2_e(o2, o3);
       if (split_group == 0) {
-        store_wt8(reinterpret_cast<uint2*>(y + row * dim) + c, __builtin_bit_cast(wt_f32x2, pk));
+        store8(reinterpret_cast<uint2*>(y + row * dim) + c, __builtin_bit_cast(wt_f32x2, pk), wt);
       } else {
         // hi | lo halves of a row of `split_group` tokens: lo = value - hi, again rounded to bf16
         bf16_t* dst = y + (row / split_group) * (2 * split_group * dim) + (row % split_group) * dim;
-        store_wt8(reinterpret_cast<uint2*>(dst) + c, __builtin_bit_cast(wt_f32x2, pk));
+        store8(reinterpret_cast<uint2*>(dst) + c, __builtin_bit_cast(wt_f32x2, pk), wt);
         uint2 lo;
         lo.x = pack2_e(o0 - __uint_as_float(pk.x << 16), o1 - __uint_as_float(pk.x & 0xFFFF0000u));
         lo.y = pack2_e(o2 - __uint_as_float(pk.y << 16), o3 - __uint_as_float(pk.y & 0xFFFF0000u));
-        store_wt8(reinterpret_cast<uint2*>(dst + split_group * dim) + c, __builtin_bit_cast(wt_f32x2, lo));
+        store8(reinterpret_cast<uint2*>(dst + split_group * dim) + c, __builtin_bit_cast(wt_f32x2, lo), wt);
       }
     }
   }
@@ -101,7 +102,7 @@ cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
-                     rows, dim, 1, 0);
+                     rows, dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -112,7 +113,7 @@ cs_status launch_rmsnorm_split(const float* x, const float* gain, float eps, bf1
   if (cs_status st = norm_check(rows, dim)) return st;
   if (group < 1 || rows % group) return fail(CS_ERR_INVALID_ARG, "rmsnorm_split: rows must be a multiple of the group");
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
-                     rows, dim, 1, group);
+                     rows, dim, 1, group, lines_exclusive(y, (int64_t)dim * 2));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -122,7 +123,7 @@ cs_status launch_layernorm(const float* x, const float* gain, const float* bias,
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y, rows,
-                     dim, 1, 0);
+                     dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -133,7 +134,7 @@ cs_status launch_pool_layernorm(const float* x, const float* gain, const float* 
   if (cs_status st = norm_check(out_rows, dim)) return st;
   if (pool < 1) return fail(CS_ERR_INVALID_ARG, "pool_layernorm: pool < 1");
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y,
-                     out_rows, dim, pool, 0);
+                     out_rows, dim, pool, 0, lines_exclusive(y, (int64_t)dim * 2));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -142,7 +143,7 @@ cs_status launch_pool_layernorm(const float* x, const float* gain, const float* 
 template <bool SRC_BF16>
 __global__ __launch_bounds__(256) void gather_cast_kernel(const void* __restrict__ src, int src_cols,
                                                           const int32_t* __restrict__ src_row,
-                                                          bf16_t* __restrict__ dst, int dst_cols, int64_t rows) {
+                                                          bf16_t* __restrict__ dst, int dst_cols, int64_t rows, bool wt) {
   const int cpr = dst_cols >> 2;
   const int64_t total = rows * cpr;
   for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256) void gather_cast_kernel(const void* __restrict
         pk.y = pack2_e(v.z, v.w);
       }
     }
-    store_wt8(dst + r * dst_cols + c, __builtin_bit_cast(wt_f32x2, pk));
+    store8(dst + r * dst_cols + c, __builtin_bit_cast(wt_f32x2, pk), wt);
   }
 }
 
@@ -171,9 +172,11 @@ cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols,
   const int64_t total = rows * (dst_cols >> 2);
   const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
   if (src_is_bf16)
-    hipLaunchKernelGGL(gather_cast_kernel<true>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows);
+    hipLaunchKernelGGL(gather_cast_kernel<true>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows,
+                       lines_exclusive(dst, 128));
   else
-    hipLaunchKernelGGL(gather_cast_kernel<false>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows);
+    hipLaunchKernelGGL(gather_cast_kernel<false>, dim3(blocks), dim3(256), 0, s, src, src_cols, src_row, dst, dst_cols, rows,
+                       lines_exclusive(dst, 128));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -230,7 +233,7 @@ cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int6
 // ---- embedding hand-off: dst[index[i], :] = src[i, :], 16 bytes per thread, rows whole
 __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ src, const int64_t* __restrict__ index,
                                                            uint4* __restrict__ dst, int64_t n_rows, int64_t dst_rows,
-                                                           int chunks_per_row, int32_t* err_flag) {
+                                                           int chunks_per_row, int32_t* err_flag, bool wt) {
   const int64_t total = n_rows * chunks_per_row;
   for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
     const int64_t r = t / chunks_per_row;
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restri
       if (err_flag && c == 0) *err_flag = 1;
       continue;
     }
-    store_wt16(dst + d * chunks_per_row + c, __builtin_bit_cast(wt_f32x4, src[t]));
+    store16(dst + d * chunks_per_row + c, __builtin_bit_cast(wt_f32x4, src[t]), wt);
   }
 }
 
@@ -252,7 +255,7 @@ cs_status launch_scatter_rows(const void* src, const int64_t* index, void* dst, 
   const int64_t total = n_rows * cpr;
   const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 8 ? (total + 255) / 256 : 65536 * 8);
   hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint4*>(src), index,
-                     static_cast<uint4*>(dst), n_rows, dst_rows, (int)cpr, err_flag);
+                     static_cast<uint4*>(dst), n_rows, dst_rows, (int)cpr, err_flag, lines_exclusive(dst, row_bytes));
   CS_HIP(hipGetLastError());
   return CS_OK;
 }

@@ -69,7 +69,7 @@ constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 template <int NB, typename T, bool ACCUM>
 __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&v)[NB][4], T* out, int64_t ld,
                                             const int32_t* row_map, int row0, int row_end, int col0, int col_end,
-                                            bool wide, const f32x4* held = nullptr) {
+                                            bool wide, bool wt, const f32x4* held = nullptr) {
   constexpr int ES = (int)sizeof(T);
   static_assert(NB * 32 * ES <= 128, "a chunk row holds 128 bytes");
   static_assert(!ACCUM || ES == 4, "accumulation is for fp32 outputs");
@@ -102,10 +102,10 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
     if constexpr (ES == 4) {
       f32x4* d4 = reinterpret_cast<f32x4*>(dst);
       if constexpr (ACCUM) *d4 = (held ? held[it] : *d4) + piece;
-      else store_wt16(d4, piece);
+      else store16(d4, piece, wt);
     } else {
       if (wide && n + 8 <= col_end) {
-        store_wt16(dst, piece);
+        store16(dst, piece, wt);
       } else {
         const f32x2 lo = {piece[0], piece[1]}, hi = {piece[2], piece[3]};
         *reinterpret_cast<f32x2*>(dst) = lo;
@@ -310,6 +310,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         }
       });
       const bool wide = (g.ld_vt & 7) == 0;
+      const bool wt_v = lines_exclusive(g.vt, g.ld_vt * 2);   // a workgroup writes 512-byte runs of a v^T row
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const float b = bv[j];
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * q + e] + b;
           store_block<2, bf16_t, false>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
-                                        N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide);
+                                        N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide, wt_v);
         }
       }
       return;
@@ -411,6 +412,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int nw = n0 + wn * WN;               // first column of this wave
   const int nl = nw + 4 * lhi;               // first column this lane holds
   const bool wide = (g.ldo & 7) == 0;
+  // write-through stores only where no 128-byte line of the output is shared with another workgroup:
+  // aligned rows, and a tile's column extent in bytes a multiple of 128
+  constexpr int OUT_ES = (EPI == EPI_F32 || EPI == EPI_GELU_F32 || EPI == EPI_RESADD_F32) ? 4 : 2;
+  constexpr int TILE_OUT_BYTES = (EPI == EPI_SWIGLU_BF16 ? BN / 2 : BN) * OUT_ES;
+  const bool wt = TILE_OUT_BYTES % 128 == 0 && lines_exclusive(g.out, g.ldo * OUT_ES);
   // QKV: byte offset of the first (cos, sin) pair of every 4-column group, once per lane (the
   // divisions by run-time sizes must not be redone for every row block)
   [[maybe_unused]] int rope_off[TN][4];
@@ -442,7 +448,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
             for (int e = 0; e < 4; ++e) v[b][q][e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
           }
         store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M,
-                                       (nw >> 1) + p0 * 32, N >> 1, wide);
+                                       (nw >> 1) + p0 * 32, N >> 1, wide, wt);
       };
       constexpr int NP = TN / 2;
 #pragma unroll
@@ -481,18 +487,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
           }
         const int col0 = nw + j0 * 32;
         if constexpr (EPI == EPI_RESADD_F32) {
-          store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true,
+          store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, false,
                                        HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
           if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
           }
         } else if constexpr (OUT_F32) {
-          store_block<NB, float, false>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true);
+          store_block<NB, float, false>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, wt);
         } else if constexpr (EPI == EPI_QKV) {
           store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0,
-                                         2 * g.hidden, wide);
+                                         2 * g.hidden, wide, wt);
         } else {
-          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide);
+          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide, wt);
           if constexpr (EPI == EPI_GELU_SPLIT) {
             // second half of the row: what the bf16 rounding of the first half dropped
 #pragma unroll
@@ -503,7 +509,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
                 v[b][q] -= __builtin_convertvector(h, f32x4);
               }
             store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, N,
-                                           wide && (N & 7) == 0);
+                                           wide && (N & 7) == 0, wt && (N & 63) == 0);
           }
         }
       };

@@ -341,3 +341,36 @@ def test_merge_major_input_order_gives_the_same_embeddings():
     b, _ = B.Encoder(replace(w.cfg, input_order="merge_major"), w.weights).cs_encode(xm, w.cu_seqlens, w.grid_thw)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and not torch.equal(x, xm)
+
+
+def test_outputs_that_do_not_start_on_a_128_byte_line():
+    """The kernels write through the L2 only where whole 128-byte lines are theirs; a destination that
+    is merely 16-byte aligned must take the plain path and give the same bits."""
+    rng = np.random.default_rng(31)
+    # hand-off into a buffer that starts 16 bytes into an allocation
+    rows, hidden, n_dst = 300, 512, 900
+    src_bits = rng.integers(0, 1 << 16, size=(rows, hidden), dtype=np.uint16)
+    dst_bits = rng.integers(0, 1 << 16, size=(n_dst, hidden), dtype=np.uint16)
+    idx = rng.permutation(n_dst)[:rows].astype(np.int64)
+    raw = torch.zeros(n_dst * hidden * 2 + 64, dtype=torch.uint8, device=DEV)
+    dst = raw[16:16 + n_dst * hidden * 2].view(torch.bfloat16).view(n_dst, hidden)
+    dst.copy_(torch.from_numpy(dst_bits.view(np.int16)).to(DEV).view(torch.bfloat16))
+    assert dst.data_ptr() % 128 == 16
+    src = torch.from_numpy(src_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    B.cs_forward_embeddings(src, torch.from_numpy(idx).to(DEV), dst)
+    torch.cuda.synchronize()
+    got = dst.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, O.forward_embeddings(src_bits, idx, dst_bits))
+    # GEMM output 16 bytes into an allocation, rows a multiple of 128 bytes
+    M, N, K = 600, 512, 256
+    A = wl.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+    W = wl.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    raw2 = torch.zeros(M * N * 2 + 64, dtype=torch.uint8, device=DEV)
+    out = raw2[16:16 + M * N * 2].view(torch.bfloat16).view(M, N)
+    ref_out = torch.empty(M, N, device=DEV, dtype=torch.bfloat16)
+    B.cs_linear_bf16(dev_bf16(A), dev_bf16(W), None, out)
+    B.cs_linear_bf16(dev_bf16(A), dev_bf16(W), None, ref_out)
+    torch.cuda.synchronize()
+    assert out.data_ptr() % 128 == 16 and ref_out.data_ptr() % 128 == 0
+    assert torch.equal(out, ref_out)
+    assert np.abs(out.float().cpu().numpy() - O.linear(A, W)).max() <= 2 ** -8 * 12 + 1e-6
