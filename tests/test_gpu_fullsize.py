@@ -107,6 +107,7 @@ def test_c3_varlen_batch():
     enc, x, out, ws = encode(w, vit_weights(w))
     check_rows("c3", out, w)
     check_forward(w, out)
+    same_bits_again(enc, x, w, out, ws)
     # batch invariance at full size: the smallest item alone gives the same rows
     it = int(np.argmin(w.grid_thw.prod(1)))
     one = w.select_items([it])
@@ -116,11 +117,19 @@ def test_c3_varlen_batch():
     assert (o1 - out[ocu[it]:ocu[it + 1]]).abs().max().item() <= 1e-2
 
 
+def same_bits_again(enc, x, w, out, ws):
+    """The same call again: identical bits (no atomics, fixed schedule, no line shared between writers)."""
+    out2, _ = enc.cs_encode(x, w.cu_seqlens, w.grid_thw, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
 def test_c4_video_clips():
     w = wl.c4_video()
     enc, x, out, ws = encode(w, vit_weights(w))
     check_rows("c4", out, w)
     check_forward(w, out)
+    same_bits_again(enc, x, w, out, ws)
 
 
 def test_c5_audio_clips():
@@ -128,3 +137,4 @@ def test_c5_audio_clips():
     enc, x, out, ws = encode(w, w.weights)
     check_rows("c5", out, w)
     check_forward(w, out)
+    same_bits_again(enc, x, w, out, ws)
