@@ -49,7 +49,8 @@ typedef enum {
   CS_ERR_INDEX = 4,       /* reserved for host-side index checks                    */
   CS_ERR_UNSUPPORTED = 5, /* a configuration the kernels are not built for          */
   CS_ERR_HIP = 6,         /* a HIP runtime call failed (text in cs_last_error)      */
-  CS_ERR_MISSING_WEIGHT = 7
+  CS_ERR_MISSING_WEIGHT = 7,
+  CS_ERR_BUSY = 8         /* cs_channel_acquire: every slot is in use; try again later */
 } cs_status;
 
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
@@ -164,6 +165,55 @@ cs_status cs_encode(cs_encoder* enc, const void* patches, const int32_t* cu_seql
 cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_index, void* dst_seq,
                                 int64_t n_rows, int64_t dst_rows, int32_t hidden, int32_t dtype,
                                 int32_t* err_flag, void* stream);
+
+/* cs_channel: the hand-off as a channel between an encoder task (producer) and an LLM task
+ * (consumer) that run on two streams of one process on one GPU.  In the paper a producer's tensor
+ * is put into a shared buffer, the consumer is told its address, copies it into its own memory, and
+ * executors wait for tensors that have not arrived yet (Sec. 3.1 "Data Forwarding", Sec. 4.3
+ * "Sidecar").  Here the shared buffer is a pool of equally sized slots in device memory, the
+ * notification is the slot number with its description (rows, width, dtype), "arrived" is a HIP
+ * event, and the consumer's copy is the placement itself (the scatter of cs_forward_embeddings
+ * reading the slot), so rows move once and never leave HBM.  No call blocks the host:
+ *
+ *   producer                                   consumer
+ *   cs_channel_acquire  -> slot, dev pointer
+ *   cs_encode(..., out_embeddings = pointer, producer stream)
+ *   cs_channel_publish(slot, rows, ...)  ----- slot number ----->  cs_channel_forward(slot, index, dst,
+ *                                                                    consumer stream)
+ *
+ * A slot is FREE, WRITING (acquired, being produced) or READY (published, not yet forwarded).
+ *  - acquire takes the lowest-numbered FREE slot and makes `producer_stream` wait until the last
+ *    consumer of that slot has read it; CS_ERR_BUSY if no slot is FREE (nothing changes; call again
+ *    after a forward), CS_ERR_WORKSPACE if bytes == 0 or bytes > slot_bytes.
+ *  - publish records the arrival event behind everything enqueued on `producer_stream` so far, which
+ *    must include all work that writes the slot; n_rows * hidden * sizeof(dtype) must not exceed the
+ *    bytes reserved (CS_ERR_SHAPE); a row must be a multiple of 16 bytes (CS_ERR_UNSUPPORTED).
+ *  - forward makes `consumer_stream` wait for the arrival, enqueues
+ *    dst_seq[placeholder_index[i], :] = slot[i, :] exactly as cs_forward_embeddings does (same
+ *    argument rules, same err_flag behaviour) and returns the slot to FREE.  A rejected call leaves
+ *    the slot READY.  With n_rows == 0 nothing is enqueued.
+ *  - release returns a WRITING or READY slot to FREE without placing it (a cancelled request);
+ *    `stream` is the stream whose work may still touch the slot, the next producer waits for it.
+ *  - describe reports a slot (any out pointer may be NULL): state, dev pointer, and for a READY slot
+ *    its rows / width / dtype and whether the arrival event has completed (a host-side poll).
+ * Using a slot in the wrong state is CS_ERR_INVALID_ARG.  Calls may come from different host
+ * threads; they are serialised inside.  create allocates the pool (n_slots * slot_bytes rounded up
+ * to 256 bytes, one hipMalloc) and two events per slot on the current device; the other calls
+ * allocate nothing.  destroy must not be called while work that uses the pool is still running.
+ * Two processes would need IPC memory handles for the pool and the events; that is not built. */
+typedef struct cs_channel cs_channel;
+typedef enum { CS_SLOT_FREE = 0, CS_SLOT_WRITING = 1, CS_SLOT_READY = 2 } cs_slot_state;
+#define CS_CHANNEL_MAX_SLOTS 1024
+cs_status cs_channel_create(int32_t n_slots, size_t slot_bytes, cs_channel** out);
+void cs_channel_destroy(cs_channel* ch);
+cs_status cs_channel_acquire(cs_channel* ch, size_t bytes, void* producer_stream, int32_t* slot, void** dev_ptr);
+cs_status cs_channel_publish(cs_channel* ch, int32_t slot, int64_t n_rows, int32_t hidden, int32_t dtype,
+                             void* producer_stream);
+cs_status cs_channel_forward(cs_channel* ch, int32_t slot, const int64_t* placeholder_index, void* dst_seq,
+                             int64_t dst_rows, int32_t* err_flag, void* consumer_stream);
+cs_status cs_channel_release(cs_channel* ch, int32_t slot, void* stream);
+cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, const void** dev_ptr, int64_t* n_rows,
+                              int32_t* hidden, int32_t* dtype, int32_t* arrived);
 
 /* Host-only (no GPU needed) view of the token plan cs_encode builds for a vit batch with this
  * configuration; also validates the batch description exactly as cs_encode does.

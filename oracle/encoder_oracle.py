@@ -256,7 +256,7 @@ def audio_encode(cfg, W: Dict[str, np.ndarray], frames: np.ndarray, cu_seqlens: 
     followed by GELU; sinusoidal positions; pre-LayerNorm blocks with full attention
     inside a clip (or, with cfg.attn_chunk > 0, inside each chunk of that many tokens of a clip:
     the block-diagonal attention long-audio encoders use; the convolutions and positions still
-    run over the whole clip, which is this build's reading); mean over frame pairs; LayerNorm;
+    run over the whole clip, which is the reading taken here); mean over frame pairs; LayerNorm;
     projection."""
     xs = []
     for i in range(len(cu_seqlens) - 1):
@@ -333,8 +333,8 @@ def pack_batch(rows: Sequence[int], row_budget: int, max_items: int) -> list:
     """First-fit in arrival order: `rows` lists the pending items' input-row counts oldest first.
     The oldest item is always taken; every later one is taken when the total stays within the
     budget and fewer than max_items are taken.  Returns the taken indices.  (The paper shares one
-    encoder between apps, Sec. 3.1 "Component Sharing", and names no batching policy; this is the
-    policy this build documents.)"""
+    encoder between apps, Sec. 3.1 "Component Sharing", and names no batching policy; first-fit is
+    the policy chosen here.)"""
     taken, total = [], 0
     for i, r in enumerate(rows):
         if len(taken) >= max_items:
@@ -358,3 +358,53 @@ def forward_embeddings(src: np.ndarray, placeholder_index: np.ndarray, dst: np.n
             continue
         out[j, :] = src[i, :]
     return out
+
+
+class ChannelModel:
+    """The hand-off channel as a sequential program: a pool of equally sized slots, each FREE,
+    WRITING or READY (Sec. 3.1 "Data Forwarding", Sec. 4.3: a producer puts its tensor in a shared
+    buffer, tells the consumer where it is, the consumer places it).  Every call happens at once
+    and in call order; whatever overlap an implementation allows must give these results.
+    Calls return a status word: "ok", "busy" (no free slot), "workspace" (tensor larger than a
+    slot, or empty), "shape" (more rows published than reserved), "invalid" (slot in the wrong
+    state or no such slot)."""
+
+    FREE, WRITING, READY = 0, 1, 2
+
+    def __init__(self, n_slots: int, slot_bytes: int):
+        self.slot_bytes = slot_bytes
+        self.state = [self.FREE] * n_slots
+        self.reserved = [0] * n_slots
+        self.rows = [None] * n_slots
+
+    def acquire(self, nbytes: int):
+        """-> (status, slot): the lowest-numbered free slot."""
+        if nbytes <= 0 or nbytes > self.slot_bytes:
+            return "workspace", -1
+        for i, st in enumerate(self.state):
+            if st == self.FREE:
+                self.state[i], self.reserved[i] = self.WRITING, nbytes
+                return "ok", i
+        return "busy", -1
+
+    def publish(self, slot: int, rows: np.ndarray) -> str:
+        if not 0 <= slot < len(self.state) or self.state[slot] != self.WRITING:
+            return "invalid"
+        if rows.nbytes > self.reserved[slot]:
+            return "shape"
+        self.rows[slot], self.state[slot] = rows.copy(), self.READY
+        return "ok"
+
+    def forward(self, slot: int, placeholder_index: np.ndarray, dst: np.ndarray):
+        """-> (status, dst after the placement)."""
+        if not 0 <= slot < len(self.state) or self.state[slot] != self.READY:
+            return "invalid", dst
+        out = forward_embeddings(self.rows[slot], placeholder_index, dst) if len(self.rows[slot]) else dst.copy()
+        self.state[slot], self.rows[slot] = self.FREE, None
+        return "ok", out
+
+    def release(self, slot: int) -> str:
+        if not 0 <= slot < len(self.state) or self.state[slot] == self.FREE:
+            return "invalid"
+        self.state[slot], self.rows[slot] = self.FREE, None
+        return "ok"

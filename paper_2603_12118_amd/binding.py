@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libcornenc.so")
 CS_F32, CS_BF16 = 0, 1
 CS_ARCH_VIT, CS_ARCH_AUDIO = 0, 1
 CS_ORDER_RASTER, CS_ORDER_MERGE_MAJOR = 0, 1
+CS_SLOT_FREE, CS_SLOT_WRITING, CS_SLOT_READY = 0, 1, 2
+CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY = 1, 2, 3, 5, 8
 STEPS = {"front": 1, "norm": 2, "qkv": 3, "attn_window": 4, "attn_full": 5, "proj": 6, "mlp_up": 7, "mlp_down": 8,
          "back": 9}
 
@@ -63,6 +65,14 @@ def lib() -> C.CDLL:
         L.cs_attention_varlen.argtypes = [vp, vp, i64, vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
         L.cs_pack_batch.argtypes = [i32p, C.c_int32, i64, C.c_int32, i32p, i32p, i32p, i32p]
         L.cs_patchify.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int32, i32p, i32p, vp]
+        L.cs_channel_create.argtypes = [C.c_int32, C.c_size_t, C.POINTER(vp)]
+        L.cs_channel_destroy.argtypes = [vp]
+        L.cs_channel_destroy.restype = None
+        L.cs_channel_acquire.argtypes = [vp, C.c_size_t, vp, i32p, C.POINTER(vp)]
+        L.cs_channel_publish.argtypes = [vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
+        L.cs_channel_forward.argtypes = [vp, C.c_int32, vp, vp, i64, vp, vp]
+        L.cs_channel_release.argtypes = [vp, C.c_int32, vp]
+        L.cs_channel_describe.argtypes = [vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(i64), i32p, i32p, i32p]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
         L.cs_encoder_time_every.argtypes = [vp, C.c_int32]
@@ -72,7 +82,9 @@ def lib() -> C.CDLL:
         L.cs_last_error.restype = C.c_char_p
         for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
-                  "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch"):
+                  "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
+                  "cs_channel_acquire", "cs_channel_publish", "cs_channel_forward", "cs_channel_release",
+                  "cs_channel_describe"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -169,7 +181,8 @@ class Encoder:
         return ms.value, n.value
 
     def cs_encode(self, patches, cu_seqlens, grid_thw, out=None, workspace=None, stream=None):
-        """patches: device tensor [N, patch_dim] of the config dtype.  Returns (out, workspace)."""
+        """patches: device tensor [N, patch_dim] of the config dtype.  Returns (out, workspace).
+        `out` may also be a device tensor view of a channel slot (Channel.slot_tensor)."""
         import torch
         cu, g = _i32(cu_seqlens), _i32(grid_thw)
         n_out, ws_bytes = self.cs_encoder_query(cu, g)
@@ -210,6 +223,77 @@ def cs_forward_embeddings(src, placeholder_index, dst_seq, err_flag=None, stream
     _check(lib().cs_forward_embeddings(src.data_ptr(), placeholder_index.data_ptr(), dst_seq.data_ptr(),
                                        src.shape[0], dst_seq.shape[0], src.shape[1], dt,
                                        err_flag.data_ptr() if err_flag is not None else None, _stream(stream)))
+
+
+class _DevView:
+    """Device memory at a raw address as an object torch.as_tensor accepts."""
+
+    def __init__(self, ptr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
+class Channel:
+    """Owns a cs_channel handle; methods carry the names of the C calls and return the status
+    where a test wants to see it (`check=False`)."""
+
+    def __init__(self, n_slots: int, slot_bytes: int):
+        self._h = C.c_void_p()
+        _check(lib().cs_channel_create(n_slots, slot_bytes, C.byref(self._h)))
+
+    def close(self) -> None:
+        if self._h:
+            lib().cs_channel_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def cs_channel_acquire(self, nbytes: int, producer_stream=None, check: bool = True):
+        """-> (status, slot, device address)"""
+        slot, ptr = C.c_int32(-1), C.c_void_p()
+        st = lib().cs_channel_acquire(self._h, nbytes, _stream(producer_stream), C.byref(slot), C.byref(ptr))
+        if check:
+            _check(st)
+        return st, slot.value, ptr.value
+
+    def slot_tensor(self, ptr: int, rows: int, hidden: int, dtype):
+        """A torch view [rows, hidden] of slot memory (no copy, no ownership)."""
+        import torch
+        nbytes = rows * hidden * torch.empty((), dtype=dtype).element_size()
+        raw = torch.as_tensor(_DevView(ptr, nbytes), device="cuda")
+        return raw.view(dtype).view(rows, hidden)
+
+    def cs_channel_publish(self, slot: int, n_rows: int, hidden: int, dtype: int, producer_stream=None, check: bool = True) -> int:
+        st = lib().cs_channel_publish(self._h, slot, n_rows, hidden, dtype, _stream(producer_stream))
+        if check:
+            _check(st)
+        return st
+
+    def cs_channel_forward(self, slot: int, placeholder_index, dst_seq, err_flag=None, consumer_stream=None,
+                           check: bool = True) -> int:
+        st = lib().cs_channel_forward(self._h, slot, placeholder_index.data_ptr(), dst_seq.data_ptr(), dst_seq.shape[0],
+                                      err_flag.data_ptr() if err_flag is not None else None, _stream(consumer_stream))
+        if check:
+            _check(st)
+        return st
+
+    def cs_channel_release(self, slot: int, stream=None, check: bool = True) -> int:
+        st = lib().cs_channel_release(self._h, slot, _stream(stream))
+        if check:
+            _check(st)
+        return st
+
+    def cs_channel_describe(self, slot: int):
+        """-> dict(state, ptr, n_rows, hidden, dtype, arrived)"""
+        state, ptr, rows = C.c_int32(), C.c_void_p(), C.c_int64()
+        hidden, dtype, arrived = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(lib().cs_channel_describe(self._h, slot, C.byref(state), C.byref(ptr), C.byref(rows), C.byref(hidden),
+                                         C.byref(dtype), C.byref(arrived)))
+        return {"state": state.value, "ptr": ptr.value, "n_rows": rows.value, "hidden": hidden.value,
+                "dtype": dtype.value, "arrived": arrived.value}
 
 
 def cs_forward_embeddings_raw(src_ptr, idx_ptr, dst_ptr, n_rows, dst_rows, hidden, dtype, err_ptr=None, stream=0) -> int:

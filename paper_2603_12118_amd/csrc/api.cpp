@@ -419,6 +419,7 @@ const char* cs_status_string(cs_status s) {
     case CS_ERR_UNSUPPORTED: return "unsupported configuration";
     case CS_ERR_HIP: return "HIP runtime error";
     case CS_ERR_MISSING_WEIGHT: return "missing weight";
+    case CS_ERR_BUSY: return "busy";
   }
   return "unknown status";
 }

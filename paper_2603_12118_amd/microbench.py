@@ -7,6 +7,9 @@
   bf16 store (`cs_linear_bf16`; the fused epilogues are timed in place by `bench.py --breakdown`),
 * `cs_forward_embeddings` at 8, 16 and 32 MB of embedding rows (the tensor sizes for which the paper
   quotes its forwarding latency, Sec. 4.3),
+* the same sizes through `cs_channel` (producer stream -> slot -> consumer stream): the time from
+  the end of the producer's last kernel to the rows being in the consumer's buffer, and the host time
+  of the three calls,
 * `cs_patchify` on the eight 448x448 images of the benchmark batch.
 
 Attention on its own at segment sizes 64 / 1024 / 8192 is what `bench.py --breakdown` reports as the
@@ -38,6 +41,39 @@ def _time(fn, n=20, warm=3):
     return e0.elapsed_time(e1) / n * 1e-3
 
 
+def _channel(B, src, idx, dst, n=20, warm=3):
+    """One tensor after the other through a two-slot channel: the producer (a copy into the slot on
+    its stream) publishes, the consumer's stream places.  Returns the mean time between an event
+    behind the producer's copy and an event behind the placement, and the host time of
+    acquire + publish + forward."""
+    import time
+    import torch
+    rows, hidden = src.shape
+    ch = B.Channel(2, src.numel() * 2)
+    prod, cons = torch.cuda.Stream(), torch.cuda.Stream()
+    pairs, host = [], 0.0
+    torch.cuda.synchronize()
+    for i in range(warm + n):
+        t0 = time.perf_counter()
+        _, slot, ptr = ch.cs_channel_acquire(src.numel() * 2, prod)
+        t1 = time.perf_counter()
+        with torch.cuda.stream(prod):
+            ch.slot_tensor(ptr, rows, hidden, torch.bfloat16).copy_(src, non_blocking=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(prod)
+        t2 = time.perf_counter()
+        ch.cs_channel_publish(slot, rows, hidden, B.CS_BF16, prod)
+        ch.cs_channel_forward(slot, idx, dst, None, cons)
+        t3 = time.perf_counter()
+        e1.record(cons)
+        torch.cuda.synchronize()       # one tensor in flight at a time: the latency, not the throughput
+        if i >= warm:
+            pairs.append(e0.elapsed_time(e1) * 1e3)
+            host += (t1 - t0) + (t3 - t2)
+    ch.close()
+    return {"us_producer_done_to_placed": sum(pairs) / n, "host_us": host / n * 1e6}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--json", action="store_true")
@@ -47,7 +83,7 @@ def main() -> int:
     dev = "cuda:0"
     g = torch.Generator(device=dev).manual_seed(1)
     res = {"mfma_ceiling_tflops": {"zero_operands": B.cs_mfma_ceiling(False), "random_operands": B.cs_mfma_ceiling(True)},
-           "gemm": [], "forward_embeddings": []}
+           "gemm": [], "forward_embeddings": [], "channel": []}
     for name, M, N, K in GEMM_SHAPES:
         A = torch.randn(M, K, device=dev, generator=g).bfloat16()
         W = (torch.randn(N, K, device=dev, generator=g) * 0.05).bfloat16()
@@ -64,6 +100,7 @@ def main() -> int:
         s = _time(lambda: B.cs_forward_embeddings(src, idx, dst))
         nbytes = rows * (2 * hidden * 2 + 8)
         res["forward_embeddings"].append({"MB": mb, "rows": rows, "us": s * 1e6, "GBs": nbytes / s / 1e9})
+        res["channel"].append({"MB": mb, "rows": rows, **_channel(B, src, idx, dst)})
         del src, dst, idx
     px = torch.rand(8 * 3 * 448 * 448, device=dev, generator=g)
     dims = [(1, 448, 448)] * 8
@@ -81,6 +118,9 @@ def main() -> int:
     print("| cs_forward_embeddings | rows | us | GB/s |\n|---|---|---|---|")
     for r in res["forward_embeddings"]:
         print(f"| {r['MB']} MB | {r['rows']} | {r['us']:.1f} | {r['GBs']:.0f} |")
+    print("| cs_channel (publish -> placed) | rows | us after the producer's last kernel | host us for the 3 calls |\n|---|---|---|---|")
+    for r in res["channel"]:
+        print(f"| {r['MB']} MB | {r['rows']} | {r['us_producer_done_to_placed']:.1f} | {r['host_us']:.1f} |")
     r = res["patchify"]
     print(f"cs_patchify, {r['workload']}: {r['us']:.1f} us, {r['GBs']:.0f} GB/s")
     return 0

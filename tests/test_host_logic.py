@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     assert {"cs_encoder_create", "cs_encode", "cs_forward_embeddings", "cs_encoder_query", "cs_encoder_destroy",
             "cs_plan_tokens", "cs_linear_bf16", "cs_attention_varlen", "cs_status_string", "cs_last_error",
             "cs_encoder_time_step", "cs_encoder_read_timing", "cs_mfma_ceiling", "cs_patchify", "cs_pack_batch",
-            "cs_encoder_time_every"} <= names
+            "cs_encoder_time_every", "cs_channel_create", "cs_channel_destroy", "cs_channel_acquire",
+            "cs_channel_publish", "cs_channel_forward", "cs_channel_release", "cs_channel_describe"} <= names
     lib = C.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in cornenc.h but not exported"
@@ -141,6 +142,23 @@ def test_forward_embeddings_argument_errors_need_no_gpu():
     assert B.cs_forward_embeddings_raw(16, 16, 16, 4, 4, 8, 9) == 1                # bad dtype
     assert B.cs_forward_embeddings_raw(8, 16, 16, 4, 4, 8, B.CS_BF16) == 1         # misaligned src
     assert B.cs_forward_embeddings_raw(0, 0, 0, 0, 4, 8, B.CS_BF16) == 0           # empty: no-op
+
+
+def test_channel_argument_errors_need_no_gpu():
+    L, h, slot, ptr = B.lib(), C.c_void_p(), C.c_int32(7), C.c_void_p(5)
+    assert L.cs_channel_create(0, 1 << 20, C.byref(h)) == B.CS_ERR_INVALID_ARG          # no slots
+    assert L.cs_channel_create(1025, 1 << 20, C.byref(h)) == B.CS_ERR_INVALID_ARG       # too many slots
+    assert L.cs_channel_create(2, 0, C.byref(h)) == B.CS_ERR_INVALID_ARG                # empty slots
+    assert L.cs_channel_create(2, 1 << 20, None) == B.CS_ERR_INVALID_ARG
+    assert not h.value
+    assert L.cs_channel_acquire(None, 16, None, C.byref(slot), C.byref(ptr)) == B.CS_ERR_INVALID_ARG
+    assert L.cs_channel_publish(None, 0, 1, 8, B.CS_BF16, None) == B.CS_ERR_INVALID_ARG
+    assert L.cs_channel_forward(None, 0, None, None, 4, None, None) == B.CS_ERR_INVALID_ARG
+    assert L.cs_channel_release(None, 0, None) == B.CS_ERR_INVALID_ARG
+    assert L.cs_channel_describe(None, 0, None, None, None, None, None, None) == B.CS_ERR_INVALID_ARG
+    assert b"NULL channel" in L.cs_last_error()
+    L.cs_channel_destroy(None)                                                           # a no-op
+    assert L.cs_status_string(B.CS_ERR_BUSY) == b"busy"
 
 
 def test_pack_batch_matches_the_checker_and_feeds_the_planner():

@@ -515,3 +515,44 @@ def test_workload_shapes():
     r = wl.round_to_bf16(x)
     assert r.tolist() == torch.tensor(x).to(torch.bfloat16).float().tolist()
     assert np.array_equal(wl.from_bits_bf16(wl.to_bits_bf16(r)), r)
+
+
+# ------------------------------------------------------------------ hand-off channel (sequential model)
+def test_channel_model_follows_a_hand_written_trace():
+    """Two slots of 64 bytes, rows of 4 uint32 (16 bytes).  Every status, slot number and buffer
+    content below is written out by hand from the rules: lowest free slot; WRITING -> READY ->
+    FREE; a placement copies row i to the row its index names, -1 skips."""
+    m = O.ChannelModel(2, 64)
+    rows_a = np.array([[1, 2, 3, 4], [5, 6, 7, 8]], np.uint32)
+    rows_b = np.array([[9, 9, 9, 9]], np.uint32)
+    dst = np.zeros((4, 4), np.uint32) + np.arange(100, 104, dtype=np.uint32)[:, None]
+    assert m.acquire(0) == ("workspace", -1) and m.acquire(65) == ("workspace", -1)
+    assert m.acquire(32) == ("ok", 0)
+    assert m.acquire(64) == ("ok", 1)
+    assert m.acquire(16) == ("busy", -1)
+    assert m.publish(0, np.zeros((3, 4), np.uint32)) == "shape"        # 48 bytes into 32 reserved
+    assert m.forward(0, np.array([0]), dst)[0] == "invalid"            # acquired, nothing published
+    assert m.publish(1, rows_b) == "ok"
+    assert m.publish(1, rows_b) == "invalid"                           # already published
+    st, d1 = m.forward(1, np.array([2]), dst)
+    assert st == "ok" and d1.tolist() == [[100] * 4, [101] * 4, [9] * 4, [103] * 4]
+    assert dst.tolist() == [[100] * 4, [101] * 4, [102] * 4, [103] * 4]  # the argument is not modified
+    assert m.forward(1, np.array([2]), dst)[0] == "invalid"            # consumed: the slot is free again
+    assert m.acquire(16) == ("ok", 1)                                  # slot 0 is still being written
+    assert m.publish(0, rows_a) == "ok"
+    st, d2 = m.forward(0, np.array([3, -1]), d1)
+    assert st == "ok" and d2.tolist() == [[100] * 4, [101] * 4, [9] * 4, [1, 2, 3, 4]]
+    assert m.release(0) == "invalid" and m.release(2) == "invalid" and m.release(-1) == "invalid"
+    assert m.release(1) == "ok" and m.state == [m.FREE, m.FREE]
+    assert m.acquire(64) == ("ok", 0)
+    assert m.publish(0, np.zeros((0, 4), np.uint32)) == "ok"           # an empty tensor may be handed over
+    st, d3 = m.forward(0, np.zeros(0, np.int64), d2)
+    assert st == "ok" and np.array_equal(d3, d2)
+
+
+def test_channel_model_keeps_what_was_published_not_what_the_array_holds_later():
+    m = O.ChannelModel(1, 16)
+    rows = np.array([[1, 2, 3, 4]], np.uint32)
+    assert m.acquire(16) == ("ok", 0) and m.publish(0, rows) == "ok"
+    rows[:] = 0
+    assert m.forward(0, np.array([0]), np.zeros((1, 4), np.uint32))[1].tolist() == [[1, 2, 3, 4]]
