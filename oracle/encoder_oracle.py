@@ -275,9 +275,56 @@ def audio_encode(cfg, W: Dict[str, np.ndarray], frames: np.ndarray, cu_seqlens: 
     return linear(z, W["post.proj.weight"], W["post.proj.bias"])
 
 
+# --------------------------------------------------------------------------
+# class-token vision tower (InternVL-style)
+# --------------------------------------------------------------------------
+def cls_block(x, W, p, cfg):
+    """Pre-LayerNorm block over one image tile's tokens ``[1 + h*w, D]``: full attention, GELU
+    MLP, and a learned per-channel scale on each branch before it joins the residual stream."""
+    N, nh, dh, D = x.shape[0], cfg.n_heads, cfg.head_dim, cfg.hidden
+    u = layernorm(x, W[p + "norm1.weight"], W[p + "norm1.bias"], cfg.norm_eps)
+    qkv = linear(u, W[p + "attn.qkv.weight"], W[p + "attn.qkv.bias"])
+    q, k, v = (qkv[:, i * D:(i + 1) * D].reshape(N, nh, dh) for i in range(3))
+    a = attention(q, k, v, np.ones((N, N), bool)).reshape(N, D)
+    x = x + W[p + "ls1"] * linear(a, W[p + "attn.proj.weight"], W[p + "attn.proj.bias"])
+    u = layernorm(x, W[p + "norm2.weight"], W[p + "norm2.bias"], cfg.norm_eps)
+    m = gelu(linear(u, W[p + "mlp.fc1.weight"], W[p + "mlp.fc1.bias"]))
+    return x + W[p + "ls2"] * linear(m, W[p + "mlp.fc2.weight"], W[p + "mlp.fc2.bias"])
+
+
+def cls_encode(cfg, W: Dict[str, np.ndarray], patches: np.ndarray, grid_thw: np.ndarray) -> np.ndarray:
+    """The encoder task of a class-token vision tower, the kind InternVL-style models use (the paper
+    names that family among the models it serves, Sec. 1 and Table 1, and says nothing of its inside): per tile
+    (item, grid (1, h, w), raster patch rows) the tokens are [class token, patches], learned
+    absolute positions are added (row 0 for the class token, row 1 + r*w + c for patch (r, c)),
+    the blocks run with full attention inside the tile, the class token is dropped, every 2x2
+    group of patches is concatenated in the order (r0c0, r0c1, r1c0, r1c1), and the projector
+    LayerNorm(4D) -> Linear -> GELU -> Linear gives one embedding row per group, in raster order
+    of the groups.  Returns ``[N / 4, out_hidden]``, tile after tile."""
+    D, outs, base = cfg.hidden, [], 0
+    g64 = np.asarray(grid_thw, np.int64)
+    for T, h, w in g64.tolist():
+        assert T == 1 and 1 + h * w == W["pos_embed"].shape[0]
+        n = h * w
+        x = linear(patches[base:base + n], W["patch_embed.weight"], W["patch_embed.bias"])
+        x = np.concatenate([np.asarray(W["cls_token"], np.float64).reshape(1, D), x], 0) + W["pos_embed"]
+        for l in range(cfg.n_layers):
+            x = cls_block(x, W, f"blocks.{l}.", cfg)
+        z = x[1:].reshape(h, w, D)
+        zc = np.stack([np.concatenate([z[2 * R, 2 * C], z[2 * R, 2 * C + 1], z[2 * R + 1, 2 * C], z[2 * R + 1, 2 * C + 1]])
+                       for R in range(h // 2) for C in range(w // 2)])
+        zc = layernorm(zc, W["merger.norm.weight"], W["merger.norm.bias"], cfg.norm_eps)
+        y = gelu(linear(zc, W["merger.fc1.weight"], W["merger.fc1.bias"]))
+        outs.append(linear(y, W["merger.fc2.weight"], W["merger.fc2.bias"]))
+        base += n
+    return np.concatenate(outs, 0)
+
+
 def encode(cfg, W, patches, cu_seqlens, grid_thw) -> np.ndarray:
     if cfg.arch == "vit":
         return vit_encode(cfg, W, patches, grid_thw)
+    if cfg.arch == "vit_cls":
+        return cls_encode(cfg, W, patches, grid_thw)
     return audio_encode(cfg, W, patches, cu_seqlens)
 
 

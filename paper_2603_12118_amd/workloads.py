@@ -59,7 +59,7 @@ def from_bits_bf16(b: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 @dataclass(frozen=True)
 class EncoderConfig:
-    arch: str = "vit"            # "vit" | "audio"
+    arch: str = "vit"            # "vit" | "audio" | "vit_cls" (class token, learned positions, LayerNorm, GELU)
     dtype: str = "bf16"          # storage type of weights and inputs: "bf16" | "f32"
     out_dtype: str = "f32"       # type of the embedding rows the encoder emits
     patch_dim: int = 1176        # vit: 3*tp*14*14 ; audio: n_mels
@@ -80,6 +80,7 @@ class EncoderConfig:
     conv_kernel: int = 3         # audio only
     input_order: str = "raster"  # vit: "raster" or "merge_major" rows inside an item
     attn_chunk: int = 0          # audio: tokens per attention chunk (0: whole clip)
+    tile_patches: Tuple[int, int] = (32, 32)   # vit_cls: patch grid of a tile (sizes the position table)
 
     @property
     def elem_bytes(self) -> int:
@@ -97,6 +98,15 @@ def vit_7b_config(n_layers: int = 32, rope_sections=(0, 20, 20), out_dtype: str 
     full = tuple(l for l in (7, 15, 23, 31) if l < n_layers)
     return EncoderConfig(arch="vit", dtype="bf16", out_dtype=out_dtype, n_layers=n_layers,
                          full_attn_layers=full, rope_sections=tuple(rope_sections))
+
+
+def vit_cls_config(n_layers: int = 24, out_dtype: str = "f32") -> EncoderConfig:
+    """A 0.3B-class class-token tower (InternVL-style): 448x448 tiles of 32x32 patches, hidden 1024,
+    16 heads of 64, MLP 4096, projector LayerNorm(4096) -> 4096 -> GELU -> 4096."""
+    return EncoderConfig(arch="vit_cls", dtype="bf16", out_dtype=out_dtype, patch_dim=588, temporal_patch=1,
+                         hidden=1024, n_heads=16, head_dim=64, n_layers=n_layers, mlp_dim=4096, merge=2,
+                         merger_hidden=4096, out_hidden=4096, window=0, full_attn_layers=(),
+                         rope_sections=(0, 0, 0), norm_eps=1e-6)
 
 
 def audio_config(n_layers: int = 32, out_dtype: str = "f32") -> EncoderConfig:
@@ -144,13 +154,35 @@ def weight_shapes(cfg: EncoderConfig) -> List[Tuple[str, Tuple[int, ...], str]]:
                     (p + "mlp.fc2.weight", (D, I), "w"), (p + "mlp.fc2.bias", (D,), "b")]
         out += [("post.norm.weight", (D,), "g"), ("post.norm.bias", (D,), "b"),
                 ("post.proj.weight", (cfg.out_hidden, D), "w"), ("post.proj.bias", (cfg.out_hidden,), "b")]
+    elif cfg.arch == "vit_cls":
+        out += [("patch_embed.weight", (D, cfg.patch_dim), "w"), ("patch_embed.bias", (D,), "b"),
+                ("cls_token", (D,), "b"), ("pos_embed", (1 + n_positions_grid(cfg), D), "b")]
+        for l in range(L):
+            p = f"blocks.{l}."
+            out += [(p + "norm1.weight", (D,), "g"), (p + "norm1.bias", (D,), "b"),
+                    (p + "attn.qkv.weight", (3 * D, D), "w"), (p + "attn.qkv.bias", (3 * D,), "b"),
+                    (p + "attn.proj.weight", (D, D), "w"), (p + "attn.proj.bias", (D,), "b"), (p + "ls1", (D,), "s"),
+                    (p + "norm2.weight", (D,), "g"), (p + "norm2.bias", (D,), "b"),
+                    (p + "mlp.fc1.weight", (I, D), "w"), (p + "mlp.fc1.bias", (I,), "b"),
+                    (p + "mlp.fc2.weight", (D, I), "w"), (p + "mlp.fc2.bias", (D,), "b"), (p + "ls2", (D,), "s")]
+        g = cfg.merge * cfg.merge * D
+        out += [("merger.norm.weight", (g,), "g"), ("merger.norm.bias", (g,), "b"),
+                ("merger.fc1.weight", (cfg.merger_hidden, g), "w"), ("merger.fc1.bias", (cfg.merger_hidden,), "b"),
+                ("merger.fc2.weight", (cfg.out_hidden, cfg.merger_hidden), "w"),
+                ("merger.fc2.bias", (cfg.out_hidden,), "b")]
     else:
         raise ValueError(cfg.arch)
     return out
 
 
+def n_positions_grid(cfg: EncoderConfig) -> int:
+    """Patches per tile of a class-token tower (its position table has one more row)."""
+    return cfg.tile_patches[0] * cfg.tile_patches[1]
+
+
 def make_weights(cfg: EncoderConfig, seed: int = 0, std: float = 0.02) -> Dict[str, np.ndarray]:
-    """Random-init weights: matrices and biases ~ N(0, std); norm gains 1 + N(0, std).
+    """Random-init weights: matrices and biases ~ N(0, std); norm gains 1 + N(0, std); the
+    branch scales of the class-token tower 0.1 + N(0, std) (such towers start them at 0.1).
     The key-projection third of the audio qkv bias is zero (that tower has no key bias)."""
     rng = np.random.default_rng(seed)
     W: Dict[str, np.ndarray] = {}
@@ -158,6 +190,8 @@ def make_weights(cfg: EncoderConfig, seed: int = 0, std: float = 0.02) -> Dict[s
         a = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
         if kind == "g":
             a = a + np.float32(1.0)
+        if kind == "s":
+            a = a + np.float32(0.1)
         if kind == "kb":
             a[cfg.hidden:2 * cfg.hidden] = 0.0
         if cfg.dtype == "bf16":
@@ -348,3 +382,17 @@ def small_vit(sizes_px=((84, 140), (252, 476), (56, 56)), n_layers: int = 3, dty
     cfg = replace(vit_7b_config(n_layers, rope_sections=rope_sections), dtype=dtype,
                   full_attn_layers=tuple(full_layers))
     return images_workload("small_vit", cfg, list(sizes_px), seq_len=1024)
+
+
+def c6_tiles(n_layers: int = 24, n_tiles: int = 8, out_dtype: str = "f32") -> Workload:
+    """Eight 448x448 tiles (1024 patches + a class token each) through the class-token tower."""
+    cfg = vit_cls_config(n_layers, out_dtype=out_dtype)
+    return images_workload("c6_tiles", cfg, [(448, 448)] * n_tiles, seq_len=2048)
+
+
+def small_cls(tile_patches=(6, 10), n_tiles: int = 3, n_layers: int = 2, dtype: str = "bf16") -> Workload:
+    """A shallow class-token tower of the 0.3B shape on a few small tiles (61 tokens each for the
+    default 6x10 grid: not a multiple of anything the kernels tile by)."""
+    cfg = replace(vit_cls_config(n_layers), dtype=dtype, tile_patches=tuple(tile_patches))
+    px = (tile_patches[0] * PATCH, tile_patches[1] * PATCH)
+    return images_workload("small_cls", cfg, [px] * n_tiles, seq_len=256)

@@ -450,6 +450,99 @@ def test_vit_batch_invariance_bitwise():
     assert np.allclose(both, np.concatenate([a, b]), atol=1e-12)
 
 
+# ------------------------------------------------------------------ class-token tower
+def _mini_cls_cfg(**kw):
+    base = dict(arch="vit_cls", dtype="f32", patch_dim=24, temporal_patch=1, hidden=32, n_heads=2, head_dim=16,
+                n_layers=3, mlp_dim=40, merge=2, merger_hidden=48, out_hidden=20, window=0, full_attn_layers=(),
+                rope_sections=(0, 0, 0), tile_patches=(4, 6))
+    base.update(kw)
+    return wl.EncoderConfig(**base)
+
+
+def _torch_cls_tower(cfg, W, patches, n_tiles):
+    """Second write-up from PyTorch pieces, organised differently from the checker: all tiles as one
+    batched tensor [B, 1 + h*w, D], library LayerNorm / attention / GELU, the 2x2 grouping by a
+    view + permute instead of explicit indices."""
+    W = {k: T64(v) for k, v in W.items()}
+    h, w = cfg.tile_patches
+    D, nh, dh = cfg.hidden, cfg.n_heads, cfg.head_dim
+    x = F.linear(T64(patches).reshape(n_tiles, h * w, -1), W["patch_embed.weight"], W["patch_embed.bias"])
+    x = torch.cat([W["cls_token"].expand(n_tiles, 1, D), x], 1) + W["pos_embed"][None]
+    for l in range(cfg.n_layers):
+        p = f"blocks.{l}."
+        u = F.layer_norm(x, (D,), W[p + "norm1.weight"], W[p + "norm1.bias"], cfg.norm_eps)
+        q, k, v = F.linear(u, W[p + "attn.qkv.weight"], W[p + "attn.qkv.bias"]).reshape(n_tiles, -1, 3, nh, dh).permute(2, 0, 3, 1, 4)
+        a = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(n_tiles, -1, D)
+        x = x + W[p + "ls1"] * F.linear(a, W[p + "attn.proj.weight"], W[p + "attn.proj.bias"])
+        u = F.layer_norm(x, (D,), W[p + "norm2.weight"], W[p + "norm2.bias"], cfg.norm_eps)
+        m = F.gelu(F.linear(u, W[p + "mlp.fc1.weight"], W[p + "mlp.fc1.bias"]))
+        x = x + W[p + "ls2"] * F.linear(m, W[p + "mlp.fc2.weight"], W[p + "mlp.fc2.bias"])
+    z = x[:, 1:].reshape(n_tiles, h // 2, 2, w // 2, 2, D).permute(0, 1, 3, 2, 4, 5).reshape(-1, 4 * D)
+    z = F.layer_norm(z, (4 * D,), W["merger.norm.weight"], W["merger.norm.bias"], cfg.norm_eps)
+    y = F.gelu(F.linear(z, W["merger.fc1.weight"], W["merger.fc1.bias"]))
+    return F.linear(y, W["merger.fc2.weight"], W["merger.fc2.bias"]).numpy()
+
+
+@pytest.mark.parametrize("tile", [(4, 6), (2, 2), (6, 4)])
+def test_cls_tower_matches_independent_composition(tile):
+    cfg = _mini_cls_cfg(tile_patches=tile)
+    W = wl.make_weights(cfg, seed=11, std=0.2)
+    n = tile[0] * tile[1]
+    patches = RNG.standard_normal((3 * n, cfg.patch_dim))
+    mine = O.cls_encode(cfg, W, patches, np.array([(1, *tile)] * 3))
+    assert mine.shape == (3 * n // 4, cfg.out_hidden)
+    assert np.allclose(mine, _torch_cls_tower(cfg, W, patches, 3), atol=1e-9)
+
+
+def test_cls_tower_with_zero_branch_scales_in_closed_form():
+    """ls1 = ls2 = 0 switches every block off: the output is the projector applied to
+    patch_embed + position, written out here with explicit indices (a 4 x 6 tile: group (R, C) is
+    patches (2R, 2C), (2R, 2C+1), (2R+1, 2C), (2R+1, 2C+1); patch (r, c) takes position row
+    1 + 6 r + c); the class token and position row 0 do not reach the output at all."""
+    cfg = _mini_cls_cfg()
+    W = wl.make_weights(cfg, seed=12, std=0.2)
+    for l in range(cfg.n_layers):
+        W[f"blocks.{l}.ls1"] = np.zeros(cfg.hidden, np.float32)
+        W[f"blocks.{l}.ls2"] = np.zeros(cfg.hidden, np.float32)
+    patches = RNG.standard_normal((24, cfg.patch_dim))
+    grid = np.array([[1, 4, 6]])
+    e = patches @ W["patch_embed.weight"].astype(np.float64).T + W["patch_embed.bias"]
+    rows = []
+    for R in range(2):
+        for C in range(3):
+            rows.append(np.concatenate([e[6 * r + c] + W["pos_embed"][1 + 6 * r + c].astype(np.float64)
+                                        for r, c in ((2 * R, 2 * C), (2 * R, 2 * C + 1), (2 * R + 1, 2 * C), (2 * R + 1, 2 * C + 1))]))
+    z = np.stack(rows)
+    z = (z - z.mean(1, keepdims=True)) / np.sqrt(z.var(1, keepdims=True) + cfg.norm_eps)
+    z = z * W["merger.norm.weight"] + W["merger.norm.bias"]
+    hid = z @ W["merger.fc1.weight"].astype(np.float64).T + W["merger.fc1.bias"]
+    hid = np.array([[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row] for row in hid])
+    want = hid @ W["merger.fc2.weight"].astype(np.float64).T + W["merger.fc2.bias"]
+    got = O.cls_encode(cfg, W, patches, grid)
+    assert np.allclose(got, want, atol=1e-10)
+    W2 = dict(W)
+    W2["cls_token"] = W["cls_token"] + 1.0
+    W2["pos_embed"] = W["pos_embed"].copy()
+    W2["pos_embed"][0] += 3.0
+    assert np.array_equal(O.cls_encode(cfg, W2, patches, grid), got)
+
+
+def test_cls_tower_class_token_is_attended_and_tiles_are_independent():
+    cfg = _mini_cls_cfg()
+    W = wl.make_weights(cfg, seed=13, std=0.2)
+    patches = RNG.standard_normal((48, cfg.patch_dim))
+    g = np.array([[1, 4, 6], [1, 4, 6]])
+    both = O.cls_encode(cfg, W, patches, g)
+    a, b = O.cls_encode(cfg, W, patches[:24], g[:1]), O.cls_encode(cfg, W, patches[24:], g[1:])
+    assert np.allclose(both, np.concatenate([a, b]), atol=1e-12)
+    W2 = dict(W)
+    # with the blocks on, the class token is a key for every patch (a change that LayerNorm does not
+    # remove: not a common offset of all channels)
+    W2["cls_token"] = W["cls_token"] + np.linspace(-1, 1, cfg.hidden).astype(np.float32)
+    assert np.abs(O.cls_encode(cfg, W2, patches[:24], g[:1]) - a).max() > 1e-4
+    assert np.allclose(O.encode(cfg, W, patches, np.array([0, 24, 48]), g), both, atol=0)
+
+
 def test_audio_tower_matches_independent_composition():
     cfg = wl.EncoderConfig(arch="audio", dtype="f32", patch_dim=6, temporal_patch=1, hidden=16, n_heads=2,
                            head_dim=8, n_layers=2, mlp_dim=24, merge=2, merger_hidden=0, out_hidden=10,
