@@ -54,7 +54,13 @@ typedef enum {
 } cs_status;
 
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
-typedef enum { CS_ARCH_VIT = 0, CS_ARCH_AUDIO = 1 } cs_arch;
+/* CS_ARCH_VIT: rotary, RMSNorm, window/full attention, SwiGLU, per-patch-norm 2x2 merger (Qwen2.5-VL-style).
+ * CS_ARCH_AUDIO: two convolutions, sinusoidal positions, LayerNorm, GELU MLP, pooling (Whisper-style).
+ * CS_ARCH_VIT_CLS: class token, learned absolute positions, LayerNorm, full attention inside a tile,
+ *   GELU MLP, a learned per-channel scale on each branch, and a projector LayerNorm(4*hidden) ->
+ *   Linear -> GELU -> Linear over 2x2 patch groups (InternVL-style; the paper names that family among
+ *   the models it serves, Sec. 1 and Table 1, and says nothing of its inside). */
+typedef enum { CS_ARCH_VIT = 0, CS_ARCH_AUDIO = 1, CS_ARCH_VIT_CLS = 2 } cs_arch;
 /* Order of an item's patch rows on input.  RASTER: (t, row, col).  MERGE_MAJOR: the order the
  * stock preprocessors of such vision towers emit, merge group by merge group: (t, row/merge,
  * col/merge, row%merge, col%merge).  The embedding rows come out in raster order of the merged
@@ -104,6 +110,14 @@ typedef struct {
  *         blocks.{l}.attn.qkv.weight/.bias  attn.proj.weight/.bias
  *         blocks.{l}.mlp.fc1.weight [mlp_dim,hidden] .bias  mlp.fc2.weight [hidden,mlp_dim] .bias
  *         post.norm.weight/.bias   post.proj.weight [out_hidden,hidden] .bias
+ *  vit_cls: patch_embed.weight [hidden,patch_dim] .bias   cls_token [hidden]
+ *         pos_embed [1 + patches per tile, hidden]  (row 0: class token; row 1 + r*w + c: patch (r,c))
+ *         blocks.{l}.norm1.weight/.bias  norm2.weight/.bias  attn.qkv.weight/.bias  attn.proj.weight/.bias
+ *         blocks.{l}.ls1 [hidden], ls2 [hidden]   (x += ls1 * attention branch;  x += ls2 * MLP branch)
+ *         blocks.{l}.mlp.fc1.weight [mlp_dim,hidden] .bias  mlp.fc2.weight [hidden,mlp_dim] .bias
+ *         merger.norm.weight/.bias [4*hidden]
+ *         merger.fc1.weight [merger_hidden, 4*hidden] .bias   merger.fc2.weight [out_hidden, merger_hidden] .bias
+ *         (window <= 0, rope_sections all 0, merge 2, hidden <= 2048)
  * A bias that is absent from the list is taken as zero; any other absent tensor is an error. */
 typedef struct {
   const char* name;
@@ -138,8 +152,11 @@ cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, con
  *  cu_seqlens      host [n_items+1], cu_seqlens[0] = 0, item i owns rows [cu[i], cu[i+1]).
  *  grid_thw        host [n_items,3] = (t, h, w) in patches, h and w multiples of `merge`,
  *                       t*h*w == cu[i+1]-cu[i].  audio: (1, 1, frames), frames a multiple of 4.
+ *                       vit_cls: an item is one tile, (1, h, w) with 1 + h*w == rows of pos_embed.
  *  out_embeddings  dev  [M, out_hidden], config.out_dtype.  vit: item i yields t*(h/2)*(w/2) rows
- *                       in raster order of the merged grid; audio: frames/4 rows; items in input
+ *                       in raster order of the merged grid (vit_cls: (h/2)*(w/2) rows per tile, group
+ *                       (R, C) = patches (2R,2C), (2R,2C+1), (2R+1,2C), (2R+1,2C+1) in that order; the
+ *                       class token yields no row); audio: frames/4 rows; items in input
  *                       order.  M = sum over items (cs_encoder_query reports it).
  *  workspace       dev, at least the size cs_encoder_query reports for this batch; contents
  *                       are scratch.  Two calls that overlap in time need two workspaces.
@@ -222,7 +239,10 @@ cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, cons
  *  src_row   [N]   raster patch row feeding internal token i
  *  out_row   [N/4] output embedding row written by internal merged token j
  *  win_cu    [n_windows+1] internal-token boundaries of the attention windows
- * Any output pointer may be NULL.  *n_windows receives the number of windows. */
+ * Any output pointer may be NULL.  *n_windows receives the number of windows.
+ * vit_cls: a tile of h*w patches has h*w + 4 internal tokens: its patches merge group by merge group,
+ * then the class token, then three padding tokens; src_row [N + 4*n_items] holds -1 for those four,
+ * out_row [N/4 + n_items] holds -1 for the row they form; there are no windows (*n_windows = 0). */
 cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
                          int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
                          int32_t win_cu_capacity, int32_t* n_windows);

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcornenc.so")
 
 CS_F32, CS_BF16 = 0, 1
-CS_ARCH_VIT, CS_ARCH_AUDIO = 0, 1
+CS_ARCH_VIT, CS_ARCH_AUDIO, CS_ARCH_VIT_CLS = 0, 1, 2
 CS_ORDER_RASTER, CS_ORDER_MERGE_MAJOR = 0, 1
 CS_SLOT_FREE, CS_SLOT_WRITING, CS_SLOT_READY = 0, 1, 2
 CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY = 1, 2, 3, 5, 8
@@ -114,7 +114,7 @@ def make_config(cfg) -> cs_encoder_config:
     """workloads.EncoderConfig -> C struct."""
     c = cs_encoder_config()
     c.struct_size = C.sizeof(cs_encoder_config)
-    c.arch = CS_ARCH_VIT if cfg.arch == "vit" else CS_ARCH_AUDIO
+    c.arch = {"vit": CS_ARCH_VIT, "audio": CS_ARCH_AUDIO, "vit_cls": CS_ARCH_VIT_CLS}[cfg.arch]
     c.dtype = CS_BF16 if cfg.dtype == "bf16" else CS_F32
     c.out_dtype = CS_BF16 if cfg.out_dtype == "bf16" else CS_F32
     for k in ("patch_dim", "hidden", "n_heads", "head_dim", "n_layers", "mlp_dim", "merge", "merger_hidden",
@@ -202,11 +202,13 @@ def cs_plan_tokens(cfg, cu_seqlens, grid_thw):
     cu, g = _i32(cu_seqlens), _i32(grid_thw)
     cc = make_config(cfg)
     n = max(int(cu[-1]), 0) if len(cu) else 0
-    src_row, out_row = np.empty(max(n, 1), np.int32), np.empty(max(n // 4, 1), np.int32)
+    n_items = g.shape[0] if g.ndim == 2 else 0
+    n_tok = n + 4 * n_items if cfg.arch == "vit_cls" else n          # class token + padding per tile
+    src_row, out_row = np.empty(max(n_tok, 1), np.int32), np.empty(max(n_tok // 4, 1), np.int32)
     win_cu, nw = np.empty(n + 2, np.int32), C.c_int32()
-    _check(lib().cs_plan_tokens(C.byref(cc), _i32p(cu), _i32p(g), g.shape[0] if g.ndim == 2 else 0, _i32p(src_row),
+    _check(lib().cs_plan_tokens(C.byref(cc), _i32p(cu), _i32p(g), n_items, _i32p(src_row),
                                 _i32p(out_row), _i32p(win_cu), n + 2, C.byref(nw)))
-    return src_row[:n], out_row[:n // 4], win_cu[:nw.value + 1].copy()
+    return src_row[:n_tok], out_row[:n_tok // 4], win_cu[:nw.value + 1].copy()
 
 
 def cs_forward_embeddings(src, placeholder_index, dst_seq, err_flag=None, stream=None) -> None:

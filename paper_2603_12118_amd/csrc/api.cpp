@@ -62,7 +62,8 @@ struct Arena {
 
 struct LayerW {
   size_t wqkv, bqkv, wo, bo, w1, b1, w2, b2;  // w1: gate|up interleaved (vit) or fc1 (audio); w2: down / fc2
-  size_t g1, be1, g2, be2;                    // norm gains and (audio) norm biases
+  size_t g1, be1, g2, be2;                    // norm gains and (LayerNorm towers) norm biases
+  size_t ls1 = 0, ls2 = 0;                    // class-token tower: per-channel scales of the two branches
 };
 
 }  // namespace cs
@@ -83,6 +84,8 @@ struct cs_encoder {
   size_t w_c1 = 0, b_c1 = 0, w_c2 = 0, b_c2 = 0, g_p = 0, be_p = 0, w_p = 0, b_p = 0, pe_tab = 0;  // audio
   size_t inv_freq = 0, axis = 0;
   int pe_positions = 0;
+  size_t b_pe = 0, be_m = 0, pos_tab = 0;    // class-token tower: patch-embed bias, projector norm bias, position table
+  int n_positions = 0;                       // rows of its position table (1 + patches per tile); row n_positions = class token + row 0
   // pinned staging for the per-batch index tables, two slots used in turn
   void* stage[2] = {nullptr, nullptr};
   size_t stage_cap[2] = {0, 0};
@@ -106,12 +109,12 @@ static cs_status check_config(const cs_encoder_config& c) {
   if (c.struct_size != sizeof(cs_encoder_config)) return fail(CS_ERR_INVALID_ARG, "config.struct_size mismatch");
   if (c.input_order != CS_ORDER_RASTER && c.input_order != CS_ORDER_MERGE_MAJOR)
     return fail(CS_ERR_INVALID_ARG, "config.input_order");
+  if (c.arch != CS_ARCH_VIT && c.arch != CS_ARCH_AUDIO && c.arch != CS_ARCH_VIT_CLS) return fail(CS_ERR_INVALID_ARG, "config.arch");
   if (c.input_order != CS_ORDER_RASTER && c.arch != CS_ARCH_VIT)
     return fail(CS_ERR_UNSUPPORTED, "config: input_order applies to vision encoders");
   if (c.attn_chunk < 0 || (c.attn_chunk & 3)) return fail(CS_ERR_INVALID_ARG, "config.attn_chunk must be a non-negative multiple of 4");
   if (c.attn_chunk != 0 && c.arch != CS_ARCH_AUDIO)
     return fail(CS_ERR_UNSUPPORTED, "config: attn_chunk applies to audio encoders");
-  if (c.arch != CS_ARCH_VIT && c.arch != CS_ARCH_AUDIO) return fail(CS_ERR_INVALID_ARG, "config.arch");
   if ((c.dtype != CS_F32 && c.dtype != CS_BF16) || (c.out_dtype != CS_F32 && c.out_dtype != CS_BF16))
     return fail(CS_ERR_INVALID_ARG, "config.dtype / out_dtype");
   if (c.hidden <= 0 || c.n_heads <= 0 || c.head_dim <= 0 || c.n_heads * c.head_dim != c.hidden)
@@ -131,6 +134,12 @@ static cs_status check_config(const cs_encoder_config& c) {
     if (c.rope_sections[0] < 0 || c.rope_sections[1] < 0 || c.rope_sections[2] < 0 || (s != 0 && s != c.head_dim / 2))
       return fail(CS_ERR_INVALID_ARG, "config: rope_sections must sum to head_dim/2 (or all be 0)");
     if (s && !(c.rope_theta > 0)) return fail(CS_ERR_INVALID_ARG, "config: rope_theta");
+  } else if (c.arch == CS_ARCH_VIT_CLS) {
+    if (c.merge != 2) return fail(CS_ERR_UNSUPPORTED, "config: merge must be 2");
+    if (c.merger_hidden <= 0) return fail(CS_ERR_INVALID_ARG, "config: merger_hidden");
+    if (c.window > 0 || c.rope_sections[0] || c.rope_sections[1] || c.rope_sections[2])
+      return fail(CS_ERR_UNSUPPORTED, "config: a class-token tower has full attention and learned positions (window <= 0, no rotary sections)");
+    if (4 * c.hidden > 8192) return fail(CS_ERR_UNSUPPORTED, "config: hidden of a class-token tower is at most 2048");
   } else {
     if (c.merge < 1 || c.merge > 8) return fail(CS_ERR_UNSUPPORTED, "config: pool must be 1..8");
     if (c.conv_kernel != 3) return fail(CS_ERR_UNSUPPORTED, "config: conv_kernel must be 3");
@@ -210,7 +219,7 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
     if (cs_status st = wb.get(p + "norm2.weight", D, t)) return st;
     L.g2 = pack_vector(A, t, D, ident);
     L.be1 = L.be2 = 0;
-    if (c.arch == CS_ARCH_AUDIO) {
+    if (c.arch != CS_ARCH_VIT) {
       if (cs_status st = wb.get(p + "norm1.bias", D, t, true)) return st;
       L.be1 = pack_vector(A, t, D, ident);
       if (cs_status st = wb.get(p + "norm2.bias", D, t, true)) return st;
@@ -224,6 +233,12 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
     if (cs_status st = wb.get(p + "attn.proj.bias", D, b, true)) return st;
     L.wo = pack_matrix(A, t, D, D, D, ident);
     L.bo = pack_vector(A, b, D, ident);
+    if (c.arch == CS_ARCH_VIT_CLS) {
+      if (cs_status st = wb.get(p + "ls1", D, t)) return st;
+      L.ls1 = pack_vector(A, t, D, ident);
+      if (cs_status st = wb.get(p + "ls2", D, t)) return st;
+      L.ls2 = pack_vector(A, t, D, ident);
+    }
     if (c.arch == CS_ARCH_VIT) {
       // gate and up rows interleaved in blocks of 32 so that one lane holds gate_j and up_j
       SrcTensor tg, tu, bg, bu;
@@ -260,12 +275,34 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
       L.b2 = pack_vector(A, b, D, ident);
     }
   }
-  if (c.arch == CS_ARCH_VIT) {
+  if (c.arch == CS_ARCH_VIT || c.arch == CS_ARCH_VIT_CLS) {
     const int64_t P = c.patch_dim, G = (int64_t)c.merge * c.merge * D, MH = c.merger_hidden, H = c.out_hidden;
     if (cs_status st = wb.get("patch_embed.weight", D * P, t)) return st;
     e->w_pe = pack_matrix(A, t, D, P, e->P_pad, ident);
-    if (cs_status st = wb.get("merger.norm.weight", D, t)) return st;
-    e->g_m = pack_vector(A, t, D, ident);
+    if (c.arch == CS_ARCH_VIT) {
+      if (cs_status st = wb.get("merger.norm.weight", D, t)) return st;
+      e->g_m = pack_vector(A, t, D, ident);
+    } else {
+      // the projector's LayerNorm runs over the concatenation of a merge group
+      if (cs_status st = wb.get("merger.norm.weight", G, t)) return st;
+      e->g_m = pack_vector(A, t, G, ident);
+      if (cs_status st = wb.get("merger.norm.bias", G, b, true)) return st;
+      e->be_m = pack_vector(A, b, G, ident);
+      if (cs_status st = wb.get("patch_embed.bias", D, b, true)) return st;
+      e->b_pe = pack_vector(A, b, D, ident);
+      // position table, and behind it the row the class token starts from (class token + position 0)
+      SrcTensor cls, pe;
+      if (cs_status st = wb.get("cls_token", D, cls)) return st;
+      auto it = wb.m.find("pos_embed");
+      if (it == wb.m.end()) return fail(CS_ERR_MISSING_WEIGHT, "missing weight: pos_embed");
+      pe = it->second;
+      if (pe.numel % D || pe.numel / D < 5 || pe.numel / D > (1 << 20))
+        return fail(CS_ERR_SHAPE, "weight pos_embed: expected [1 + patches per tile, hidden]");
+      e->n_positions = (int)(pe.numel / D);
+      e->pos_tab = A.alloc((size_t)(e->n_positions + 1) * D * 4);
+      for (int64_t i = 0; i < pe.numel; ++i) A.f32(e->pos_tab)[i] = pe.at(i);
+      for (int64_t i = 0; i < D; ++i) A.f32(e->pos_tab)[pe.numel + i] = cls.at(i) + pe.at(i);
+    }
     if (cs_status st = wb.get("merger.fc1.weight", MH * G, t)) return st;
     if (cs_status st = wb.get("merger.fc1.bias", MH, b, true)) return st;
     // The merger runs with split operands: its two inputs are carried as bf16 hi + bf16 lo
@@ -361,9 +398,9 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   w.ld_vt = round_up(N, 64);   // rows of v^T start on 128-byte lines (write-through stores need that)
   w.vt = take((size_t)D * w.ld_vt * 2);
   size_t big = (size_t)N * e->I_pad * 2;                                   // MLP activation
-  if (c.arch == CS_ARCH_VIT) {
+  if (c.arch != CS_ARCH_AUDIO) {
     big = std::max(big, (size_t)N * e->P_pad * 2);                          // gathered patches
-    big = std::max(big, (size_t)p.n_out * e->MH_pad * 4);                   // merger hidden, hi|lo
+    big = std::max(big, (size_t)p.n_groups * e->MH_pad * 4);                // merger hidden, hi|lo
   } else {
     // padded mel frames, then padded conv1 output, both alive during conv1
     big = std::max(big, (size_t)round_up(p.n_pad_rows * c.patch_dim * 2, 256) + (size_t)p.n_pad_rows * D * 2);
@@ -398,6 +435,7 @@ struct StepTimer {
 
 static cs_status make_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items, BatchPlan& p) {
   if (e->cfg.arch == CS_ARCH_VIT) return build_vit_plan(e->cfg, cu, grid, n_items, p);
+  if (e->cfg.arch == CS_ARCH_VIT_CLS) return build_cls_plan(e->cfg, e->n_positions, cu, grid, n_items, p);
   cs_status st = build_audio_plan(e->cfg, cu, grid, n_items, p);
   if (st) return st;
   for (int i = 0; i < n_items; ++i)
@@ -448,7 +486,7 @@ cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* we
   const cs_encoder_config& c = e->cfg;
   e->P_pad = (int)round_up(c.patch_dim, 64);
   e->I_pad = (int)round_up(c.mlp_dim, 64);
-  e->MH_pad = c.arch == CS_ARCH_VIT ? (int)round_up(c.merger_hidden, 64) : 0;
+  e->MH_pad = c.arch != CS_ARCH_AUDIO ? (int)round_up(c.merger_hidden, 64) : 0;
   e->half = c.head_dim / 2;
   e->rope = c.arch == CS_ARCH_VIT && (c.rope_sections[0] + c.rope_sections[1] + c.rope_sections[2]) > 0;
   Arena A;
@@ -525,14 +563,22 @@ cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seql
                          int32_t win_cu_capacity, int32_t* n_windows) {
   if (!config) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: NULL config");
   if (cs_status st = check_config(*config)) return st;
-  if (config->arch != CS_ARCH_VIT) return fail(CS_ERR_UNSUPPORTED, "cs_plan_tokens: vision encoders only");
+  if (config->arch == CS_ARCH_AUDIO) return fail(CS_ERR_UNSUPPORTED, "cs_plan_tokens: vision encoders only");
   BatchPlan p;
-  if (cs_status st = build_vit_plan(*config, cu_seqlens, grid_thw, n_items, p)) return st;
+  if (config->arch == CS_ARCH_VIT) {
+    if (cs_status st = build_vit_plan(*config, cu_seqlens, grid_thw, n_items, p)) return st;
+  } else {
+    // without an encoder the position table is taken to fit the first tile
+    if (!grid_thw || n_items <= 0) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: no items");
+    const int64_t n_pos = 1 + (int64_t)grid_thw[1] * grid_thw[2];
+    if (n_pos < 5 || n_pos > (1 << 20)) return fail(CS_ERR_SHAPE, "cs_plan_tokens: tile size");
+    if (cs_status st = build_cls_plan(*config, (int32_t)n_pos, cu_seqlens, grid_thw, n_items, p)) return st;
+  }
   if (src_row) memcpy(src_row, p.blob.data() + p.off_src_row, (size_t)p.n_tok * 4);
-  if (out_row) memcpy(out_row, p.blob.data() + p.off_out_row, (size_t)p.n_out * 4);
-  const int32_t nw = (int32_t)p.win_cu.size() - 1;
+  if (out_row) memcpy(out_row, p.blob.data() + p.off_out_row, (size_t)p.n_groups * 4);
+  const int32_t nw = p.win_cu.empty() ? 0 : (int32_t)p.win_cu.size() - 1;
   if (n_windows) *n_windows = nw;
-  if (win_cu) {
+  if (win_cu && !p.win_cu.empty()) {
     if (win_cu_capacity < nw + 1) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: win_cu_capacity too small");
     memcpy(win_cu, p.win_cu.data(), (size_t)(nw + 1) * 4);
   }
@@ -582,7 +628,7 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   bf16_t* vt = reinterpret_cast<bf16_t*>(ws + w.vt);
   bf16_t* big = reinterpret_cast<bf16_t*>(ws + w.big);
   float* rope_cs = reinterpret_cast<float*>(ws + w.rope);
-  const bool vit = c.arch == CS_ARCH_VIT;
+  const bool vit = c.arch == CS_ARCH_VIT, cls = c.arch == CS_ARCH_VIT_CLS;
   const int out_epi = c.out_dtype == CS_BF16 ? EPI_BF16 : EPI_F32;
 
   auto gemm = [&](int epi, const bf16_t* A, int64_t lda, size_t W, size_t bias, void* out, int64_t ldo, int64_t M,
@@ -591,6 +637,13 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.bias = bias ? e->ptr<float>(bias) : nullptr;
     g.out = out; g.ldo = ldo; g.row_map = row_map; g.M = (int32_t)M; g.N = (int32_t)Nn; g.K = (int32_t)K;
     return launch_gemm(epi, g, stream);
+  };
+  // x += scale * (A W^T + bias): a branch of the class-token tower joining the residual stream
+  auto gemm_scaled = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K) {
+    GemmArgs g = {};
+    g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.bias = e->ptr<float>(bias); g.col_scale = e->ptr<float>(scale);
+    g.out = x; g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D; g.K = (int32_t)K;
+    return launch_gemm(EPI_RESADD_SCALED_F32, g, stream);
   };
 
   // ---- front end: tokens into the fp32 residual stream x [N, D]
@@ -601,6 +654,12 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
       if (e->rope)
         if (cs_status st = launch_rope_table(plan + p.off_pos, e->ptr<int32_t>(e->axis), e->ptr<float>(e->inv_freq), e->half, rope_cs, N, stream)) return st;
       if (cs_status st = gemm(EPI_F32, big, e->P_pad, e->w_pe, 0, x, D, N, D, e->P_pad, nullptr)) return st;
+    } else if (cls) {
+      // patch rows in internal order (zero rows where the class token and the padding go), embedded with
+      // bias; then the positions are added and the class-token and padding rows are written
+      if (cs_status st = launch_gather_cast(patches, c.dtype == CS_BF16, c.patch_dim, plan + p.off_src_row, big, e->P_pad, N, stream)) return st;
+      if (cs_status st = gemm(EPI_F32, big, e->P_pad, e->w_pe, e->b_pe, x, D, N, D, e->P_pad, nullptr)) return st;
+      if (cs_status st = launch_place_tokens(x, e->ptr<float>(e->pos_tab), plan + p.off_pos, e->n_positions, N, (int32_t)D, stream)) return st;
     } else {
       const int64_t R = p.n_pad_rows, C = c.patch_dim;
       bf16_t* melp = big;
@@ -646,7 +705,8 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);
-      if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st;
+      if (cls) { if (cs_status st = gemm_scaled(attn, D, L.wo, L.bo, L.ls1, D)) return st; }
+      else { if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st; }
     }
     if (cs_status st = norm(L.g2, L.be2)) return st;
     {
@@ -656,16 +716,21 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     }
     {
       StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
-      if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st;
+      if (cls) { if (cs_status st = gemm_scaled(big, e->I_pad, L.w2, L.b2, L.ls2, e->I_pad)) return st; }
+      else { if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st; }
     }
   }
 
   // ---- back end: merged / pooled tokens -> embedding rows
   {
     StepTimer tm(e, CS_STEP_BACK, stream);
-    if (vit) {
-      const int64_t M = p.n_out, G = (int64_t)c.merge * c.merge * D;
-      if (cs_status st = launch_rmsnorm_split(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, c.merge * c.merge, stream)) return st;
+    if (vit || cls) {
+      const int64_t M = p.n_groups, G = (int64_t)c.merge * c.merge * D;
+      if (vit) {
+        if (cs_status st = launch_rmsnorm_split(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, c.merge * c.merge, stream)) return st;
+      } else {
+        if (cs_status st = launch_layernorm_wide_split(x, e->ptr<float>(e->g_m), e->ptr<float>(e->be_m), c.norm_eps, xn, M, (int32_t)G, stream)) return st;
+      }
       if (cs_status st = gemm(EPI_GELU_SPLIT, xn, 2 * G, e->w_m1, e->b_m1, big, 2 * e->MH_pad, M, e->MH_pad, 2 * G, nullptr)) return st;
       if (cs_status st = gemm(out_epi, big, 2 * e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, 2 * e->MH_pad, plan + p.off_out_row)) return st;
     } else {

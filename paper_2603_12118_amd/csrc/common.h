@@ -33,7 +33,8 @@ enum GemmEpilogue {
   EPI_RESADD_F32 = 4, // out += acc + bias   (fp32 residual stream)
   EPI_SWIGLU_BF16 = 5,// weight rows interleaved in blocks of 32: gate | up; out[:, j] = silu(g) * u
   EPI_QKV = 6,        // q,k: bias, rotary, (q: scale) -> bf16 row-major; v: bias -> bf16 transposed
-  EPI_GELU_SPLIT = 7  // v = gelu(acc + bias) -> bf16 hi at column n and bf16 lo = v - hi at column N + n
+  EPI_GELU_SPLIT = 7, // v = gelu(acc + bias) -> bf16 hi at column n and bf16 lo = v - hi at column N + n
+  EPI_RESADD_SCALED_F32 = 8  // out += col_scale * (acc + bias)   (a learned per-channel scale on the branch)
 };
 
 struct GemmArgs {
@@ -41,6 +42,7 @@ struct GemmArgs {
   int64_t lda;
   const bf16_t* W;   // [N, K], K % 64 == 0
   const float* bias; // [N] or nullptr
+  const float* col_scale;  // [N], EPI_RESADD_SCALED_F32 only
   void* out;         // [*, ldo]
   int64_t ldo;
   const int32_t* row_map;  // nullptr, or destination row per m (negative: skip)
@@ -135,6 +137,12 @@ cs_status launch_gather_cast(const void* src, int src_is_bf16, int32_t src_cols,
 // out[n, j] = (cos, sin) of pos[n, axis[j]] * inv_freq[j]
 cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float* inv_freq, int32_t half,
                             float* cos_sin_out, int64_t n_tok, hipStream_t s);
+// class-token towers: pos[r] >= 0: x[r] += table[pos[r]];  -1: x[r] = table[class_row];  -2: x[r] = 0
+cs_status launch_place_tokens(float* x, const float* table, const int32_t* pos, int32_t class_row, int64_t rows,
+                              int32_t dim, hipStream_t s);
+// y[r, 0:dim) = bf16 hi parts of layernorm(x[r, 0:dim)), y[r, dim:2*dim) = lo parts; one workgroup per row, dim <= 8192
+cs_status launch_layernorm_wide_split(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
+                                      int64_t rows, int32_t dim, hipStream_t s);
 // x[r, :] += table[pos[r], :]
 cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim,
                           hipStream_t s);

@@ -230,6 +230,109 @@ cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int6
   return CS_OK;
 }
 
+// ---- class-token towers: learned positions onto the patch embeddings, the class-token row, zero padding rows
+__global__ __launch_bounds__(256) void place_tokens_kernel(float* __restrict__ x, const float* __restrict__ table,
+                                                           const int32_t* __restrict__ pos, int class_row, int64_t rows,
+                                                           int dim) {
+  const int cpr = dim >> 2;
+  const int64_t total = rows * cpr;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / cpr;
+    const int c = (int)(t - r * cpr);
+    const int p = pos[r];
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p >= 0) {
+      v = reinterpret_cast<const float4*>(x + r * dim)[c];
+      const float4 a = reinterpret_cast<const float4*>(table + (int64_t)p * dim)[c];
+      v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+    } else if (p == -1) {
+      v = reinterpret_cast<const float4*>(table + (int64_t)class_row * dim)[c];
+    }
+    reinterpret_cast<float4*>(x + r * dim)[c] = v;
+  }
+}
+
+cs_status launch_place_tokens(float* x, const float* table, const int32_t* pos, int32_t class_row, int64_t rows,
+                              int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (dim & 3) return fail(CS_ERR_UNSUPPORTED, "place_tokens: dim must be a multiple of 4");
+  const int64_t total = rows * (dim >> 2);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
+  hipLaunchKernelGGL(place_tokens_kernel, dim3(blocks), dim3(256), 0, s, x, table, pos, class_row, rows, dim);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// ---- LayerNorm over wide rows (the concatenation of a merge group), one workgroup per row, output as
+// bf16 hi | lo halves.  A thread keeps up to WIDE_MAX_V4 float4 of the row in registers.
+constexpr int WIDE_MAX_V4 = 8;  // 256 threads * 8 * 4 = 8192 floats
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();                       // red may still be read from the previous reduction
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void layernorm_wide_split_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                                   const float* __restrict__ bias, float eps,
+                                                                   bf16_t* __restrict__ y, int dim, bool wt) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.x;
+  const int nv = dim >> 2;
+  float4 v[WIDE_MAX_V4];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < WIDE_MAX_V4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < nv) v[i] = reinterpret_cast<const float4*>(x + row * dim)[c];
+    s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  }
+  const float mean = block_sum_256(s, red) / dim;
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < WIDE_MAX_V4; ++i) {
+    if (threadIdx.x + 256 * i < nv) {
+      const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      ss += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+  const float rstd = rsqrtf(block_sum_256(ss, red) / dim + eps);
+  bf16_t* dst = y + row * (2 * (int64_t)dim);
+#pragma unroll
+  for (int i = 0; i < WIDE_MAX_V4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    if (c < nv) {
+      const float4 g = reinterpret_cast<const float4*>(gain)[c];
+      const float4 b = reinterpret_cast<const float4*>(bias)[c];
+      const float o0 = (v[i].x - mean) * rstd * g.x + b.x, o1 = (v[i].y - mean) * rstd * g.y + b.y;
+      const float o2 = (v[i].z - mean) * rstd * g.z + b.z, o3 = (v[i].w - mean) * rstd * g.w + b.w;
+      uint2 pk;
+      pk.x = pack2_e(o0, o1);
+      pk.y = pack2_e(o2, o3);
+      store8(reinterpret_cast<uint2*>(dst) + c, __builtin_bit_cast(wt_f32x2, pk), wt);
+      uint2 lo;
+      lo.x = pack2_e(o0 - __uint_as_float(pk.x << 16), o1 - __uint_as_float(pk.x & 0xFFFF0000u));
+      lo.y = pack2_e(o2 - __uint_as_float(pk.y << 16), o3 - __uint_as_float(pk.y & 0xFFFF0000u));
+      store8(reinterpret_cast<uint2*>(dst + dim) + c, __builtin_bit_cast(wt_f32x2, lo), wt);
+    }
+  }
+}
+
+cs_status launch_layernorm_wide_split(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
+                                      int64_t rows, int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if (dim <= 0 || (dim & 3) || dim > 256 * 4 * WIDE_MAX_V4)
+    return fail(CS_ERR_UNSUPPORTED, "layernorm_wide: dim must be a multiple of 4, at most 8192");
+  if (rows > 0x7fffffff) return fail(CS_ERR_UNSUPPORTED, "layernorm_wide: too many rows");
+  if (!gain || !bias) return fail(CS_ERR_INVALID_ARG, "layernorm_wide: gain and bias are needed");
+  hipLaunchKernelGGL(layernorm_wide_split_kernel, dim3((unsigned)rows), dim3(256), 0, s, x, gain, bias, eps, y, dim,
+                     lines_exclusive(y, (int64_t)dim * 2));
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
 // ---- embedding hand-off: dst[index[i], :] = src[i, :], 16 bytes per thread, rows whole
 __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ src, const int64_t* __restrict__ index,
                                                            uint4* __restrict__ dst, int64_t n_rows, int64_t dst_rows,

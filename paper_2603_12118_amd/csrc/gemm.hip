@@ -337,8 +337,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
   // With eight waves there is room for one row block only: it is fetched before the last K slice,
   // and each chunk's registers are refilled for the next row block as soon as the chunk is stored.
-  constexpr bool HOLD = EPI == EPI_RESADD_F32 && NWAVES <= 4;
-  constexpr bool HOLD_ROW = EPI == EPI_RESADD_F32 && NWAVES > 4;
+  constexpr bool RESADD = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SCALED_F32;
+  constexpr bool HOLD = RESADD && NWAVES <= 4;
+  constexpr bool HOLD_ROW = RESADD && NWAVES > 4;
   [[maybe_unused]] f32x4 held[HOLD ? TM : 1][(HOLD || HOLD_ROW) ? TN : 1][4];
   [[maybe_unused]] auto fetch_old = [&](int i, int j, f32x4 (&dst)[4]) {
     const int r = lane >> 3, c = (lane & 7) * 4;
@@ -359,6 +360,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // The bias of the lane's columns is fetched there too (a load inside the epilogue waits out its
   // latency once per chunk).
   f32x4 bias_r[TN][4];
+  [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][4];
   main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -367,6 +369,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         const int n = n0 + wn * WN + 4 * lhi + j * 32 + 8 * q;
         bias_r[j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (g.bias && n < N) bias_r[j][q] = *reinterpret_cast<const f32x4*>(g.bias + n);
+        if constexpr (EPI == EPI_RESADD_SCALED_F32) {
+          scale_r[j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (n < N) scale_r[j][q] = *reinterpret_cast<const f32x4*>(g.col_scale + n);
+        }
       }
     if constexpr (HOLD) {
 #pragma unroll
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const bool wide = (g.ldo & 7) == 0;
   // write-through stores only where no 128-byte line of the output is shared with another workgroup:
   // aligned rows, and a tile's column extent in bytes a multiple of 128
-  constexpr int OUT_ES = (EPI == EPI_F32 || EPI == EPI_GELU_F32 || EPI == EPI_RESADD_F32) ? 4 : 2;
+  constexpr int OUT_ES = (EPI == EPI_F32 || EPI == EPI_GELU_F32 || RESADD) ? 4 : 2;
   constexpr int TILE_OUT_BYTES = (EPI == EPI_SWIGLU_BF16 ? BN / 2 : BN) * OUT_ES;
   const bool wt = TILE_OUT_BYTES % 128 == 0 && lines_exclusive(g.out, g.ldo * OUT_ES);
   // QKV: byte offset of the first (cos, sin) pair of every 4-column group, once per lane (the
@@ -455,7 +461,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       for (int p0 = 0; p0 + 1 < NP; p0 += 2) emit(int_tag<2>{}, p0);
       if constexpr (NP & 1) emit(int_tag<1>{}, NP - 1);
     } else {
-      constexpr bool OUT_F32 = EPI == EPI_F32 || EPI == EPI_GELU_F32 || EPI == EPI_RESADD_F32;
+      constexpr bool OUT_F32 = EPI == EPI_F32 || EPI == EPI_GELU_F32 || RESADD;
       auto emit = [&](auto tag, int j0) {
         constexpr int NB = decltype(tag)::value;
         f32x4 v[NB][4];
@@ -469,6 +475,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
             t += bias_r[j][q];
+            if constexpr (EPI == EPI_RESADD_SCALED_F32) t *= scale_r[j][q];
             if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) t[e] = gelu_erf(t[e]);
@@ -486,7 +493,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
             v[b][q] = t;
           }
         const int col0 = nw + j0 * 32;
-        if constexpr (EPI == EPI_RESADD_F32) {
+        if constexpr (RESADD) {
           store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, false,
                                        HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
           if constexpr (HOLD_ROW) {
@@ -572,6 +579,10 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream) {
     case EPI_GELU_F32: return launch_epi<EPI_GELU_F32>(g, stream);
     case EPI_GELU_SPLIT: return launch_epi<EPI_GELU_SPLIT>(g, stream);
     case EPI_RESADD_F32: return launch_epi<EPI_RESADD_F32>(g, stream);
+    case EPI_RESADD_SCALED_F32:
+      if (!g.col_scale || (reinterpret_cast<uintptr_t>(g.col_scale) & 15))
+        return fail(CS_ERR_INVALID_ARG, "gemm: the scaled residual epilogue needs a 16-byte aligned col_scale");
+      return launch_epi<EPI_RESADD_SCALED_F32>(g, stream);
     case EPI_SWIGLU_BF16:
       if (g.N & 63) return fail(CS_ERR_UNSUPPORTED, "gemm: swiglu needs N % 64 == 0");
       return launch_epi<EPI_SWIGLU_BF16>(g, stream);

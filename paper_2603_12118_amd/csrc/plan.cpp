@@ -54,7 +54,7 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
   const int64_t N = cu[n_items];
   p = BatchPlan();
   p.n_in = p.n_tok = N;
-  p.n_out = N / (mg * mg);
+  p.n_out = p.n_groups = N / (mg * mg);
   std::vector<int32_t> src_row, pos, out_row, win_work, full_work;
   src_row.reserve(N);
   pos.reserve(3 * N);
@@ -111,6 +111,71 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
   return CS_OK;
 }
 
+// Class-token tower: a tile of h x w patches becomes h*w + 4 internal tokens: the patches in
+// merge-group order (2x2 groups row-major, row-major inside a group), then the class token, then
+// three padding tokens, so that every tile starts on a multiple of four tokens and [n_tok, D] viewed
+// as [n_tok/4, 4D] is the projector's input (one row per merge group, plus one row per tile made
+// of the class token and the padding, which is computed and dropped).  Attention: every token of
+// the tile is a query (the padding too, so that its rows stay finite), the keys are the patches and
+// the class token.
+cs_status build_cls_plan(const cs_encoder_config& cfg, int32_t n_positions, const int32_t* cu, const int32_t* grid,
+                         int32_t n_items, BatchPlan& p) {
+  if (cs_status st = check_batch(cu, grid, n_items)) return st;
+  const int mg = cfg.merge;
+  int64_t n_tok = 0;
+  for (int i = 0; i < n_items; ++i) {
+    const int64_t T = grid[3 * i], h = grid[3 * i + 1], w = grid[3 * i + 2];
+    if (T != 1) return fail(CS_ERR_SHAPE, "item " + std::to_string(i) + ": tiles of a class-token tower have t == 1");
+    if (h % mg || w % mg) return fail(CS_ERR_SHAPE, "item " + std::to_string(i) + ": h and w must be multiples of the merge size");
+    if (1 + h * w != n_positions)
+      return fail(CS_ERR_SHAPE, "item " + std::to_string(i) + ": 1 + h*w must equal the rows of the position table (" +
+                                    std::to_string(n_positions) + ")");
+    n_tok += h * w + 4;
+  }
+  if (n_tok > std::numeric_limits<int32_t>::max() / 8) return fail(CS_ERR_SHAPE, "batch too large");
+  p = BatchPlan();
+  p.n_in = cu[n_items];
+  p.n_tok = n_tok;
+  p.n_out = p.n_in / (mg * mg);
+  p.n_groups = n_tok / 4;
+  std::vector<int32_t> src_row, pos, out_row, full_work;
+  src_row.reserve(n_tok);
+  pos.reserve(n_tok);
+  out_row.reserve(p.n_groups);
+  int64_t out_base = 0;
+  for (int i = 0; i < n_items; ++i) {
+    const int h = grid[3 * i + 1], w = grid[3 * i + 2];
+    const int start = (int)src_row.size();
+    for (int R = 0; R < h; R += mg)
+      for (int C = 0; C < w; C += mg) {
+        out_row.push_back((int32_t)(out_base + (int64_t)(R / mg) * (w / mg) + C / mg));
+        for (int dr = 0; dr < mg; ++dr)
+          for (int dc = 0; dc < mg; ++dc) {
+            src_row.push_back(cu[i] + (R + dr) * w + C + dc);
+            pos.push_back(1 + (R + dr) * w + C + dc);
+          }
+      }
+    src_row.insert(src_row.end(), 4, -1);
+    pos.push_back(-1);               // the class token
+    pos.insert(pos.end(), 3, -2);    // padding
+    out_row.push_back(-1);
+    const int keys_end = start + h * w + 1, end = start + h * w + 4;
+    for (int q = start; q < end; q += 256) push_work(full_work, q, std::min(q + 256, end), start, keys_end);
+    out_base += (int64_t)(h / mg) * (w / mg);
+  }
+  auto put = [&](const std::vector<int32_t>& v) {
+    const size_t o = blob_section(p.blob, v.size());
+    std::copy(v.begin(), v.end(), p.blob.begin() + o);
+    return o;
+  };
+  p.off_src_row = put(src_row);
+  p.off_pos = put(pos);
+  p.off_out_row = put(out_row);
+  p.off_full_work = put(full_work);
+  p.n_full_work = (int32_t)(full_work.size() / 4);
+  return CS_OK;
+}
+
 // Audio: item i has F_i mel frames.  The two k=3 convolutions run as GEMMs over zero-padded,
 // frame-major buffers in which clip i owns F_i + 2 rows (one zero row before and after), so
 // that output frame t reads three consecutive rows starting at padded row t (stride 1) or 2t
@@ -126,7 +191,7 @@ cs_status build_audio_plan(const cs_encoder_config& cfg, const int32_t* cu, cons
   p = BatchPlan();
   p.n_in = cu[n_items];
   p.n_tok = p.n_in / 2;
-  p.n_out = p.n_tok / cfg.merge;
+  p.n_out = p.n_groups = p.n_tok / cfg.merge;
   p.n_pad_rows = p.n_in + 2 * (int64_t)n_items;
   std::vector<int32_t> mel_src(p.n_pad_rows, -1), c1_map(p.n_pad_rows - 2, -1), c2_map(p.n_pad_rows / 2 - 1, -1);
   std::vector<int32_t> zero_rows, pos(p.n_tok), full_work;

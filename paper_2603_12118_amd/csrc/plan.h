@@ -12,6 +12,7 @@ struct BatchPlan {
   int64_t n_in = 0;    // input rows (patches or mel frames)
   int64_t n_tok = 0;   // transformer tokens
   int64_t n_out = 0;   // embedding rows written
+  int64_t n_groups = 0; // rows of the merger's GEMMs (class-token towers: n_out plus one dropped row per tile)
   std::vector<int32_t> blob;
   // vit
   size_t off_src_row = 0;   // [n_tok]   raster patch row of internal token i
@@ -35,6 +36,9 @@ struct BatchPlan {
 
 cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu_seqlens, const int32_t* grid_thw,
                          int32_t n_items, BatchPlan& plan);
+// Class-token tower: `n_positions` = rows of its position table (1 + patches per tile).
+cs_status build_cls_plan(const cs_encoder_config& cfg, int32_t n_positions, const int32_t* cu_seqlens,
+                         const int32_t* grid_thw, int32_t n_items, BatchPlan& plan);
 cs_status build_audio_plan(const cs_encoder_config& cfg, const int32_t* cu_seqlens, const int32_t* grid_thw,
                            int32_t n_items, BatchPlan& plan);
 

@@ -378,3 +378,37 @@ def test_outputs_that_do_not_start_on_a_128_byte_line():
     assert out.data_ptr() % 128 == 16 and ref_out.data_ptr() % 128 == 0
     assert torch.equal(out, ref_out)
     assert np.abs(out.float().cpu().numpy() - O.linear(A, W)).max() <= 2 ** -8 * 12 + 1e-6
+
+
+# ------------------------------------------------------------------ class-token tower
+@pytest.mark.parametrize("tile,n_tiles", [((6, 10), 3), ((2, 2), 1), ((16, 18), 2), ((32, 32), 1)])
+def test_encode_class_token_tower(tile, n_tiles):
+    """Tiles of 61, 5, 289 and 1025 tokens (none a multiple of what the kernels tile by): class token,
+    learned positions, LayerNorm, full attention with the class token as a key, scaled branches,
+    LayerNorm(4D) projector; several tiles per call."""
+    w = wl.small_cls(tile_patches=tile, n_tiles=n_tiles, n_layers=2)
+    ref = O.encode(w.cfg, w.weights, w.patches, w.cu_seqlens, w.grid_thw)
+    enc, out = run_encode(w)
+    assert out.shape == (n_tiles * tile[0] * tile[1] // 4, w.cfg.out_hidden)
+    check_embeddings(out, ref, f"class-token tower, tiles {tile} x {n_tiles}")
+    out2, _ = enc.cs_encode(dev_input(w), w.cu_seqlens, w.grid_thw)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out)
+    if n_tiles > 1:                                   # a tile alone gives what it gives inside the batch
+        one = w.select_items([n_tiles - 1])
+        o1, _ = enc.cs_encode(dev_input(one), one.cu_seqlens, one.grid_thw)
+        torch.cuda.synchronize()
+        assert (o1 - out[-o1.shape[0]:]).abs().max().item() <= 1e-2
+
+
+def test_class_token_tower_rejects_what_it_cannot_run():
+    w = wl.small_cls(tile_patches=(6, 10), n_tiles=1, n_layers=1)
+    enc = B.Encoder(w.cfg, w.weights)
+    x = dev_input(w)
+    with pytest.raises(B.CsError):                    # a tile that does not fit the position table
+        enc.cs_encode(x[:48], np.array([0, 48], np.int32), np.array([[1, 6, 8]], np.int32))
+    with pytest.raises(B.CsError):                    # window attention is not part of this tower
+        B.Encoder(replace(w.cfg, window=8), w.weights)
+    no_scale = {k: v for k, v in w.weights.items() if not k.endswith("ls1")}
+    with pytest.raises(B.CsError):
+        B.Encoder(w.cfg, no_scale)

@@ -4,6 +4,7 @@ with brute-force enumeration written here.  No compute call is made (no GPU need
 import ctypes as C
 import os
 import re
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -111,6 +112,36 @@ def test_plan_full_attention_config_keeps_merge_groups():
     src, out_row, win_cu = B.cs_plan_tokens(cfg, [0, 256], [[1, 16, 16]])
     assert len(win_cu) == 1                                            # no windows
     assert np.array_equal(src.reshape(-1, 4), O.merge_index(np.array([[1, 16, 16]]), 2)[out_row])
+
+
+def test_plan_of_a_class_token_tower_by_definition():
+    """Tiles of 4x6 and 6x4 patches (25 positions each): per tile the patches merge group by merge
+    group, then four rows without a source (class token, padding); merged row j feeds output row
+    (R, C) of its tile and the row made of the class token and the padding feeds none."""
+    cfg = replace(wl.vit_cls_config(2), tile_patches=(4, 6))
+    grid = np.array([[1, 4, 6], [1, 6, 4], [1, 4, 6]], np.int32)
+    cu = np.array([0, 24, 48, 72], np.int32)
+    src, out_row, win_cu = B.cs_plan_tokens(cfg, cu, grid)
+    want_src, want_out, base, obase = [], [], 0, 0
+    for (_, h, w) in grid.tolist():
+        for R in range(h // 2):
+            for Cc in range(w // 2):
+                want_out.append(obase + R * (w // 2) + Cc)
+                want_src += [base + (2 * R + dr) * w + 2 * Cc + dc for dr in (0, 1) for dc in (0, 1)]
+        want_src += [-1] * 4
+        want_out.append(-1)
+        base += h * w
+        obase += h * w // 4
+    assert src.tolist() == want_src and out_row.tolist() == want_out and len(win_cu) == 1
+    # the same groups the checker concatenates: its merge index, tile by tile
+    groups = np.array([r for r in src.tolist() if r >= 0]).reshape(-1, 4)
+    assert np.array_equal(groups[np.argsort([o for o in out_row.tolist() if o >= 0])],
+                          O.merge_index(grid, 2).reshape(-1, 4))
+    for bad_grid, bad_cu in (([[1, 4, 6], [1, 4, 4]], [0, 24, 40]),      # a tile that does not fit the position table
+                             ([[2, 4, 6]], [0, 48]),                     # t != 1
+                             ([[1, 5, 5]], [0, 25])):                    # odd sides
+        with pytest.raises(B.CsError):
+            B.cs_plan_tokens(cfg, np.array(bad_cu, np.int32), np.array(bad_grid, np.int32))
 
 
 @pytest.mark.parametrize("cu,grid,status", [
