@@ -44,6 +44,17 @@ def algorithmic_flops(cfg, grid_thw) -> dict:
         f["mlp_up"] = 2 * N * D * 2 * I * L
         f["mlp_down"] = 2 * N * I * D * L
         f["back"] = 2 * M * 4 * D * cfg.merger_hidden + 2 * M * cfg.merger_hidden * cfg.out_hidden
+    elif cfg.arch == "vit_cls":
+        # tokens per tile: its patches and the class token; the projector runs on the patches only
+        tok = n_item + 1
+        M = N // 4
+        f["front"] = 2 * N * cfg.patch_dim * D
+        f["attn_window"] = 0
+        f["attn_full"] = 4 * int((tok ** 2).sum()) * D * L
+        N = int(tok.sum())
+        f["mlp_up"] = 2 * N * D * I * L
+        f["mlp_down"] = 2 * N * I * D * L
+        f["back"] = 2 * M * 4 * D * cfg.merger_hidden + 2 * M * cfg.merger_hidden * cfg.out_hidden
     else:
         frames = n_item
         N = int(frames.sum()) // 2
@@ -64,7 +75,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the path separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -80,7 +91,8 @@ def main() -> int:
     from paper_2603_12118_amd import workloads as wl
 
     t0 = time.time()
-    w = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio}[args.workload](out_dtype="bf16")
+    w = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio,
+         "c6": wl.c6_tiles}[args.workload](out_dtype="bf16")
     weights = w.weights
     dev = "cuda:0"
     enc = B.Encoder(w.cfg, weights)
@@ -130,8 +142,8 @@ def main() -> int:
     dom_tflops = dom_flops / (dom_avg_ms * 1e-3) / 1e12
 
     res = {
-        "metric": "encoder_patches_per_s" if w.cfg.arch == "vit" else "encoder_mel_frames_per_s",
-        "value": n_in / (ms * 1e-3), "unit": "patches/s" if w.cfg.arch == "vit" else "frames/s",
+        "metric": "encoder_patches_per_s" if w.cfg.arch != "audio" else "encoder_mel_frames_per_s",
+        "value": n_in / (ms * 1e-3), "unit": "patches/s" if w.cfg.arch != "audio" else "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "items": w.n_items, "input_rows": n_in, "embedding_rows": int(n_out),

@@ -122,6 +122,8 @@ void attn_kernel(AttnArgs a) {
     }
   };
 
+  // a wave whose queries lie beyond the item (the last query block of a sequence) only helps to stage the tiles
+  const bool live = qw < w.q1;
   load_tile(w.kv0);
   for (int kv = w.kv0; kv < (SINGLE ? w.kv0 + 1 : w.kv1); kv += 64) {
     if (!SINGLE) __syncthreads();  // previous tile fully consumed
@@ -129,6 +131,7 @@ void attn_kernel(AttnArgs a) {
     __syncthreads();
     if (!SINGLE && kv + 64 < w.kv1) load_tile(kv + 64);
     __builtin_amdgcn_sched_barrier(0);
+    if (!SINGLE && !live) continue;
 
     // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
     f32x16 s[QT][2];

@@ -198,7 +198,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
 // passed the last barrier after reading it and nothing was loaded into it since.
 // before_last() runs between the last barrier and the last slice's MFMAs: global loads it issues
 // are in flight while those execute.
-template <int BM, int BN, int WGM, int WGN, bool W_FIRST, typename F>
+template <int BM, int BN, int WGM, int WGN, bool W_FIRST, bool RAGGED, typename F>
 __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem, int m0, int n0,
                                           f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], F&& before_last) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -241,6 +241,20 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   }
   const int KT = K >> 6;
   issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
+  // RAGGED (chosen at launch when the last tile row is a noticeable share of a launch whose M is not a
+  // multiple of BM): a wave none of whose rows exist only moves its share of the slices, so that
+  // workgroup finishes in the time its live waves need, each alone on its SIMD.  A separate
+  // instantiation: the extra path costs the others registers they do not have.
+  if (RAGGED && m0 + wm * WM >= M) {
+    for (int kt = 0; kt < KT - 1; ++kt) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, kt + 1, smem + ((kt + 1) & 1) * STAGE_BYTES, wave);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    return;   // nothing to fetch for the epilogue either: it skips every row block of this wave
+  }
   for (int kt = 0; kt < KT - 1; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
@@ -258,7 +272,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
 template <int V>
 struct int_tag { static constexpr int value = V; };
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -302,7 +316,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       // column n = one v dimension, registers = rows (tokens); written as rows of the transposed
       // v buffer, 64 tokens of one dimension per chunk row.
       float bv[TN];
-      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [&] {
+      main_loop<BM, BN, WGM, WGN, false, RAGGED>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int n = n0 + wn * WN + j * 32 + l31;
@@ -361,7 +375,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // latency once per chunk).
   f32x4 bias_r[TN][4];
   [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][4];
-  main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
+  main_loop<BM, BN, WGM, WGN, true, RAGGED>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -533,11 +547,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
-static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
+template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
+static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-    constexpr int LDS = 2 * (BM + BN) * 128;
-  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI>;
+  constexpr int LDS = 2 * (BM + BN) * 128;
+  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, RAGGED>;
   static bool attr_set = false;  // one attribute call per instantiation
   if (!attr_set) {
     CS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
@@ -549,17 +563,29 @@ static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
   return CS_OK;
 }
 
+template <int BM, int BN, int WGM, int WGN, int EPI>
+static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
+  // the ragged variant where the last, partly empty tile row is at least 1/64 of the tile rows
+  if (g.M % BM != 0 && (g.M + BM - 1) / BM <= 64) return launch_one<BM, BN, WGM, WGN, EPI, true>(g, stream);
+  return launch_one<BM, BN, WGM, WGN, EPI, false>(g, stream);
+}
+
 template <int EPI>
 static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // Tile choice by the number of workgroups it yields for the 256 CUs.
   const int64_t tm = (g.M + 255) / 256;
   const int64_t big = tm * ((g.N + 255) / 256);
   const bool big_ok = EPI != EPI_QKV || (2 * g.hidden) % 256 == 0;
-  if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+  // (the scaled residual epilogue spills registers with eight waves and with 160-wide wave tiles: it
+  // takes the 256 x 128 or 128 x 128 tiles)
+  constexpr bool EIGHT_WAVES_OK = EPI != EPI_RESADD_SCALED_F32;
+  if (EIGHT_WAVES_OK && big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
     // workgroups, one round of the chip at M = 8192
-    if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+    if (EIGHT_WAVES_OK && g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+    // the same for N = 1024: 256 x 128 tiles
+    if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
   }
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }

@@ -5,7 +5,7 @@ GPU library.  The encoder treats every item of a batch independently (block-diag
 so the checker is run on single items of the full-size workloads and a sample of their output
 rows is stored; the GPU tests run the whole batch and compare those rows.
 
-    python tests/golden/make_expected.py [c2 c3 c4 c5]
+    python tests/golden/make_expected.py [c2 c3 c4 c5 c6]
 
 Output: tests/golden/<workload>_item<i>.npz with
     rows   int64 [R]            row numbers inside the item's embedding tensor
@@ -25,7 +25,7 @@ from paper_2603_12118_amd import workloads as wl            # noqa: E402
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 # workload -> items whose embeddings are stored (c3: the smallest image and a mid-sized one)
-ITEMS = {"c2": [0, 5], "c3": None, "c4": [1], "c5": [3]}
+ITEMS = {"c2": [0, 5], "c3": None, "c4": [1], "c5": [3], "c6": [0, 6]}
 N_ROWS = 12
 
 
@@ -43,7 +43,8 @@ def c3_items(w) -> list:
 
 def main(names):
     for name in names:
-        w = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio}[name]()
+        w = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio,
+             "c6": wl.c6_tiles}[name]()
         items = ITEMS[name] if ITEMS[name] is not None else c3_items(w)
         W = w.weights
         for it in items:
@@ -58,4 +59,4 @@ def main(names):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1:] or ["c2", "c3", "c4", "c5"])
+    main(sys.argv[1:] or ["c2", "c3", "c4", "c5", "c6"])
