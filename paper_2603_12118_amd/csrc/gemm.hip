@@ -272,8 +272,16 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
 template <int V>
 struct int_tag { static constexpr int value = V; };
 
+// A 64-row tile for the rows behind the last full tile row exists when every wave can own whole
+// 32-column blocks of it (and the epilogue has no pairing of column blocks).
+template <int BN, int WGM, int WGN, int EPI>
+constexpr bool light_tail() {
+  return EPI != EPI_SWIGLU_BF16 && (BN / (WGM * WGN)) % 32 == 0 && (BN / (WGM * WGN)) >= 32;
+}
+
+// One output tile: K loop and epilogue.
 template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+__device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
@@ -282,29 +290,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
   static_assert(NWAVES * CHUNK_BYTES <= STAGE_BYTES, "the epilogue chunks live in the idle stage buffer");
 
-  extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N;
   const int l31 = lane & 31, lhi = lane >> 5;
-
-  // workgroup -> tile.  Consecutive workgroups land on different XCDs (b % 8), each with its own
-  // L2, so every XCD gets a contiguous range of tile ids; ids walk the tile grid in bands of GROUP_M
-  // tile rows, row index fastest, so the ~32 tiles an XCD runs at a time form a GROUP_M x 8 block
-  // that shares GROUP_M slices of A and 8 slices of W per k-step (an L2 miss on every W byte
-  // otherwise: measured 427 clocks average L2 read latency and the L1 miss queue full 58 % of the time).
-  constexpr int GROUP_M = 4;
-  const int tiles_n = (N + BN - 1) / BN, tiles_m = (M + BM - 1) / BM;
-  const int nb = gridDim.x;
-  int bid = blockIdx.x;
-  {
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int per = nb >> 3, rem = nb & 7;
-    bid = xcd * per + (xcd < rem ? xcd : rem) + idx;
-  }
-  const int band = bid / (GROUP_M * tiles_n), in_band = bid - band * (GROUP_M * tiles_n);
-  const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
-  const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
@@ -548,6 +537,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int M = g.M, N = g.N;
+  const int tiles_n = (N + BN - 1) / BN;
+  int tiles_m = (M + BM - 1) / BM;
+  int nb = gridDim.x;
+  // RAGGED with a light tail: the workgroups behind those of the full tile rows take the remaining
+  // rows in 64-row tiles (same threads, every wave a 64 x BN/waves strip): they stream the same W
+  // slices but do a quarter of the MFMAs, so the partly empty last tile row costs microseconds
+  // instead of a round of the chip.
+  constexpr bool LIGHT = RAGGED && light_tail<BN, WGM, WGN, EPI>();
+  if constexpr (LIGHT) {
+    const int full_m = M / BM, n_main = full_m * tiles_n;
+    if ((int)blockIdx.x >= n_main) {
+      const int t = blockIdx.x - n_main;
+      const int tail_m = (M - full_m * BM + 63) / 64;
+      tile_body<64, BN, 1, WGM * WGN, EPI, false>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      return;
+    }
+    tiles_m = full_m;
+    nb = n_main;
+  }
+
+  // workgroup -> tile.  Consecutive workgroups land on different XCDs (b % 8), each with its own
+  // L2, so every XCD gets a contiguous range of tile ids; ids walk the tile grid in bands of GROUP_M
+  // tile rows, row index fastest, so the ~32 tiles an XCD runs at a time form a GROUP_M x 8 block
+  // that shares GROUP_M slices of A and 8 slices of W per k-step (an L2 miss on every W byte
+  // otherwise: measured 427 clocks average L2 read latency and the L1 miss queue full 58 % of the time).
+  constexpr int GROUP_M = 4;
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int per = nb >> 3, rem = nb & 7;
+    bid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  const int band = bid / (GROUP_M * tiles_n), in_band = bid - band * (GROUP_M * tiles_n);
+  const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
+  const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
+  tile_body<BM, BN, WGM, WGN, EPI, RAGGED && !LIGHT>(g, smem, m0, n0);
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int LDS = 2 * (BM + BN) * 128;
@@ -557,7 +588,10 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
     CS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
     attr_set = true;
   }
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const int tiles_n = (g.N + BN - 1) / BN;
+  int tiles = ((g.M + BM - 1) / BM) * tiles_n;
+  if (RAGGED && light_tail<BN, WGM, WGN, EPI>())   // full tile rows, then the remaining rows in 64-row tiles
+    tiles = (g.M / BM) * tiles_n + ((g.M % BM + 63) / 64) * tiles_n;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(NT), LDS, stream, g);
   CS_HIP(hipGetLastError());
   return CS_OK;
