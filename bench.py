@@ -76,6 +76,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "c6"])
+    ap.add_argument("--items", type=int, default=0,
+                    help="number of items in the batch (images, clips, tiles) instead of the workload's own")
     ap.add_argument("--breakdown", action="store_true", help="also time every step of the path separately")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -91,8 +93,10 @@ def main() -> int:
     from paper_2603_12118_amd import workloads as wl
 
     t0 = time.time()
-    w = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio,
-         "c6": wl.c6_tiles}[args.workload](out_dtype="bf16")
+    make = {"c2": wl.c2_images, "c3": wl.c3_varlen, "c4": wl.c4_video, "c5": wl.c5_audio, "c6": wl.c6_tiles}[args.workload]
+    size = {{"c2": "n_images", "c3": "n_images", "c4": "n_clips", "c5": "n_clips", "c6": "n_tiles"}[args.workload]: args.items} \
+        if args.items > 0 else {}
+    w = make(out_dtype="bf16", **size)
     weights = w.weights
     dev = "cuda:0"
     enc = B.Encoder(w.cfg, weights)
