@@ -175,6 +175,10 @@ def main() -> int:
     res["forward_embeddings"] = {"us_per_call": us, "algorithmic_bytes": bytes_moved,
                                  "achieved_GBs": bytes_moved / (us * 1e-6) / 1e9, "peak_GBs": PEAK_HBM_GBS}
 
+    # what a bare MFMA loop sustains on this board, next to the path's rate: with zero operands (nominal
+    # clock) and with random operands (the board at its power limit, as it is during the step)
+    res["mfma_ceiling_tflops"] = {"zero_operands": B.cs_mfma_ceiling(False), "random_operands": B.cs_mfma_ceiling(True)}
+
     if args.breakdown:
         bd = {}
         for name, sid in B.STEPS.items():
