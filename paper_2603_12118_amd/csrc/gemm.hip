@@ -198,7 +198,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
 // passed the last barrier after reading it and nothing was loaded into it since.
 // before_last() runs between the last barrier and the last slice's MFMAs: global loads it issues
 // are in flight while those execute.
-template <int BM, int BN, int WGM, int WGN, bool W_FIRST, bool RAGGED, typename F>
+template <int BM, int BN, int WGM, int WGN, bool W_FIRST, typename F>
 __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem, int m0, int n0,
                                           f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], F&& before_last) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -241,20 +241,6 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   }
   const int KT = K >> 6;
   issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
-  // RAGGED (chosen at launch when the last tile row is a noticeable share of a launch whose M is not a
-  // multiple of BM): a wave none of whose rows exist only moves its share of the slices, so that
-  // workgroup finishes in the time its live waves need, each alone on its SIMD.  A separate
-  // instantiation: the extra path costs the others registers they do not have.
-  if (RAGGED && m0 + wm * WM >= M) {
-    for (int kt = 0; kt < KT - 1; ++kt) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, kt + 1, smem + ((kt + 1) & 1) * STAGE_BYTES, wave);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    return;   // nothing to fetch for the epilogue either: it skips every row block of this wave
-  }
   for (int kt = 0; kt < KT - 1; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
@@ -280,7 +266,7 @@ constexpr bool light_tail() {
 }
 
 // One output tile: K loop and epilogue.
-template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
+template <int BM, int BN, int WGM, int WGN, int EPI>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -305,7 +291,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
       // column n = one v dimension, registers = rows (tokens); written as rows of the transposed
       // v buffer, 64 tokens of one dimension per chunk row.
       float bv[TN];
-      main_loop<BM, BN, WGM, WGN, false, RAGGED>(g, smem, m0, n0, acc, [&] {
+      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int n = n0 + wn * WN + j * 32 + l31;
@@ -364,7 +350,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // latency once per chunk).
   f32x4 bias_r[TN][4];
   [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][4];
-  main_loop<BM, BN, WGM, WGN, true, RAGGED>(g, smem, m0, n0, acc, [&] {
+  main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -536,24 +522,26 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool LIGHT_TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int M = g.M, N = g.N;
   const int tiles_n = (N + BN - 1) / BN;
   int tiles_m = (M + BM - 1) / BM;
   int nb = gridDim.x;
-  // RAGGED with a light tail: the workgroups behind those of the full tile rows take the remaining
-  // rows in 64-row tiles (same threads, every wave a 64 x BN/waves strip): they stream the same W
-  // slices but do a quarter of the MFMAs, so the partly empty last tile row costs microseconds
-  // instead of a round of the chip.
-  constexpr bool LIGHT = RAGGED && light_tail<BN, WGM, WGN, EPI>();
+  // LIGHT_TAIL (a separate instantiation, chosen at launch when M is not a multiple of BM and the last,
+  // partly empty tile row is a noticeable share of the launch): the workgroups behind those of the
+  // full tile rows take the remaining rows in 64-row tiles (same threads, every wave a 64 x BN/waves
+  // strip): they stream the same W slices but do a quarter of the MFMAs, so that tile row costs
+  // microseconds instead of a round of the chip.
+  constexpr bool LIGHT = LIGHT_TAIL;
+  static_assert(!LIGHT_TAIL || light_tail<BN, WGM, WGN, EPI>(), "no 64-row tile for this shape");
   if constexpr (LIGHT) {
     const int full_m = M / BM, n_main = full_m * tiles_n;
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI, false>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -575,14 +563,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int band = bid / (GROUP_M * tiles_n), in_band = bid - band * (GROUP_M * tiles_n);
   const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
   const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-  tile_body<BM, BN, WGM, WGN, EPI, RAGGED && !LIGHT>(g, smem, m0, n0);
+  tile_body<BM, BN, WGM, WGN, EPI>(g, smem, m0, n0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool RAGGED>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool LIGHT_TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int LDS = 2 * (BM + BN) * 128;
-  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, RAGGED>;
+  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, LIGHT_TAIL>;
   static bool attr_set = false;  // one attribute call per instantiation
   if (!attr_set) {
     CS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
@@ -590,7 +578,7 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   }
   const int tiles_n = (g.N + BN - 1) / BN;
   int tiles = ((g.M + BM - 1) / BM) * tiles_n;
-  if (RAGGED && light_tail<BN, WGM, WGN, EPI>())   // full tile rows, then the remaining rows in 64-row tiles
+  if (LIGHT_TAIL)   // full tile rows, then the remaining rows in 64-row tiles
     tiles = (g.M / BM) * tiles_n + ((g.M % BM + 63) / 64) * tiles_n;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(NT), LDS, stream, g);
   CS_HIP(hipGetLastError());
@@ -599,8 +587,10 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
 static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
-  // the ragged variant where the last, partly empty tile row is at least 1/64 of the tile rows
-  if (g.M % BM != 0 && (g.M + BM - 1) / BM <= 64) return launch_one<BM, BN, WGM, WGN, EPI, true>(g, stream);
+  // the light-tail variant where the last, partly empty tile row is at least 1/64 of the tile rows
+  if constexpr (light_tail<BN, WGM, WGN, EPI>()) {
+    if (g.M % BM != 0 && (g.M + BM - 1) / BM <= 64) return launch_one<BM, BN, WGM, WGN, EPI, true>(g, stream);
+  }
   return launch_one<BM, BN, WGM, WGN, EPI, false>(g, stream);
 }
 
@@ -613,11 +603,15 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // (the scaled residual epilogue spills registers with eight waves and with 160-wide wave tiles: it
   // takes the 256 x 128 or 128 x 128 tiles)
   constexpr bool EIGHT_WAVES_OK = EPI != EPI_RESADD_SCALED_F32;
-  if (EIGHT_WAVES_OK && big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+  if constexpr (EIGHT_WAVES_OK) {
+    if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+  }
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
     // workgroups, one round of the chip at M = 8192
-    if (EIGHT_WAVES_OK && g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+    if constexpr (EIGHT_WAVES_OK) {
+      if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+    }
     // the same for N = 1024: 256 x 128 tiles
     if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
   }
