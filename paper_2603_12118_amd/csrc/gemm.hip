@@ -604,7 +604,8 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // takes the 256 x 128 or 128 x 128 tiles)
   constexpr bool EIGHT_WAVES_OK = EPI != EPI_RESADD_SCALED_F32;
   if constexpr (EIGHT_WAVES_OK) {
-    if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+    // ... at least a round and a half of the chip, or one nearly full round
+    if ((big >= 384 || (big >= 160 && big <= 256)) && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
