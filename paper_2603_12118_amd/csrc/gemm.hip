@@ -604,8 +604,8 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // takes the 256 x 128 or 128 x 128 tiles)
   constexpr bool EIGHT_WAVES_OK = EPI != EPI_RESADD_SCALED_F32;
   if constexpr (EIGHT_WAVES_OK) {
-    // ... at least a round and a half of the chip, or one nearly full round
-    if ((big >= 384 || (big >= 160 && big <= 256)) && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+    // 256 x 256 for a round and a half of the chip or more
+    if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
@@ -615,6 +615,11 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     }
     // the same for N = 1024: 256 x 128 tiles
     if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
+  }
+  if constexpr (EIGHT_WAVES_OK) {
+    // 256 x 256 also when it fills one round to 5/8 or more (batches of 2 - 4 images: 2 - 7 % faster than
+    // 128 x 128 tiles; at 120 workgroups it loses)
+    if (big >= 160 && big <= 256 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }
