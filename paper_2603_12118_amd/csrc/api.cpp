@@ -375,9 +375,26 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
 
 // ---- workspace layout -----------------------------------------------------------------------
 struct Workspace {
-  size_t plan, rope, x, xn, attn, qk, vt, big, total;
+  size_t plan, rope, x, xn, attn, qk, vt, big, parts, total;
   int64_t ld_vt;
+  bool split_k;   // small batches: the residual GEMMs run split over K into `parts`
 };
+
+// Residual GEMMs of small batches (few workgroups, long K loops) are split over K: up to this many parts
+constexpr int MAX_K_PARTS = 4;
+constexpr int64_t SPLIT_K_MAX_TOKENS = 2560;
+
+// Parts for x += A W^T with M rows, N columns, K deep on 128 x 128 tiles: as many (at most MAX_K_PARTS)
+// as divide the K slices evenly, leave four slices or more per part and keep the launch within 640 workgroups.
+static int k_parts(int64_t M, int64_t N, int64_t K) {
+  const int64_t wgs = ((M + 127) / 128) * ((N + 127) / 128);
+  if (wgs > 160) return 1;
+  const int64_t kt = K / 64;
+  int best = 1;
+  for (int s = 2; s <= MAX_K_PARTS; ++s)
+    if (kt % s == 0 && kt / s >= 4 && wgs * s <= 640) best = s;
+  return best;
+}
 
 static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   const cs_encoder_config& c = e->cfg;
@@ -406,6 +423,8 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
     big = std::max(big, (size_t)round_up(p.n_pad_rows * c.patch_dim * 2, 256) + (size_t)p.n_pad_rows * D * 2);
   }
   w.big = take(big);
+  w.split_k = N <= SPLIT_K_MAX_TOKENS;
+  w.parts = take(w.split_k ? (size_t)MAX_K_PARTS * N * D * 4 : 0);
   w.total = off;
   return w;
 }
@@ -638,12 +657,22 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     g.out = out; g.ldo = ldo; g.row_map = row_map; g.M = (int32_t)M; g.N = (int32_t)Nn; g.K = (int32_t)K;
     return launch_gemm(epi, g, stream);
   };
-  // x += scale * (A W^T + bias): a branch of the class-token tower joining the residual stream
-  auto gemm_scaled = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K) {
+  // x += [scale *] (A W^T + bias): a branch joining the residual stream (scale: class-token tower).
+  // Small batches: partial sums over parts of K into the workspace (more workgroups, shorter K loops),
+  // then one pass that adds them to x in a fixed order.
+  float* parts = reinterpret_cast<float*>(ws + w.parts);
+  auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K) -> cs_status {
     GemmArgs g = {};
-    g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.bias = e->ptr<float>(bias); g.col_scale = e->ptr<float>(scale);
-    g.out = x; g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D; g.K = (int32_t)K;
-    return launch_gemm(EPI_RESADD_SCALED_F32, g, stream);
+    g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D;
+    const int S = w.split_k ? k_parts(N, D, K) : 1;
+    if (S > 1) {
+      g.ldw = K; g.K = (int32_t)(K / S); g.splits = S; g.split_stride = N * D; g.out = parts;
+      if (cs_status st = launch_gemm(EPI_F32, g, stream)) return st;
+      return launch_add_partials(x, parts, S, N * D, e->ptr<float>(bias), scale ? e->ptr<float>(scale) : nullptr, N, (int32_t)D, stream);
+    }
+    g.bias = e->ptr<float>(bias); g.out = x; g.K = (int32_t)K;
+    if (scale) g.col_scale = e->ptr<float>(scale);
+    return launch_gemm(scale ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32, g, stream);
   };
 
   // ---- front end: tokens into the fp32 residual stream x [N, D]
@@ -705,8 +734,7 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);
-      if (cls) { if (cs_status st = gemm_scaled(attn, D, L.wo, L.bo, L.ls1, D)) return st; }
-      else { if (cs_status st = gemm(EPI_RESADD_F32, attn, D, L.wo, L.bo, x, D, N, D, D, nullptr)) return st; }
+      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D)) return st;
     }
     if (cs_status st = norm(L.g2, L.be2)) return st;
     {
@@ -716,8 +744,7 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     }
     {
       StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
-      if (cls) { if (cs_status st = gemm_scaled(big, e->I_pad, L.w2, L.b2, L.ls2, e->I_pad)) return st; }
-      else { if (cs_status st = gemm(EPI_RESADD_F32, big, e->I_pad, L.w2, L.b2, x, D, N, D, e->I_pad, nullptr)) return st; }
+      if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad)) return st;
     }
   }
 

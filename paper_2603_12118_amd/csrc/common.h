@@ -40,13 +40,18 @@ enum GemmEpilogue {
 struct GemmArgs {
   const bf16_t* A;   // [M, lda]
   int64_t lda;
-  const bf16_t* W;   // [N, K], K % 64 == 0
+  const bf16_t* W;   // [N, ldw], K % 64 == 0
+  int64_t ldw;       // row pitch of W in elements; 0 means K
   const float* bias; // [N] or nullptr
   const float* col_scale;  // [N], EPI_RESADD_SCALED_F32 only
   void* out;         // [*, ldo]
   int64_t ldo;
   const int32_t* row_map;  // nullptr, or destination row per m (negative: skip)
   int32_t M, N, K;
+  // split K: workgroups with blockIdx.y = s compute columns [s*K, (s+1)*K) of A and W (K is the length of
+  // one part) and write to out + s * split_stride elements; splits <= 1: one part
+  int32_t splits;
+  int64_t split_stride;
   // EPI_QKV only
   bf16_t* vt;        // [hidden, ld_vt]
   int64_t ld_vt;
@@ -143,6 +148,9 @@ cs_status launch_place_tokens(float* x, const float* table, const int32_t* pos, 
 // y[r, 0:dim) = bf16 hi parts of layernorm(x[r, 0:dim)), y[r, dim:2*dim) = lo parts; one workgroup per row, dim <= 8192
 cs_status launch_layernorm_wide_split(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
                                       int64_t rows, int32_t dim, hipStream_t s);
+// x[r, n] += scale[n] * (sum over s of parts[s*stride + r*dim + n] + bias[n]); scale / bias may be NULL (1 / 0)
+cs_status launch_add_partials(float* x, const float* parts, int32_t n_parts, int64_t stride, const float* bias,
+                              const float* scale, int64_t rows, int32_t dim, hipStream_t s);
 // x[r, :] += table[pos[r], :]
 cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim,
                           hipStream_t s);

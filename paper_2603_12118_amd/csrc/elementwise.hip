@@ -205,6 +205,45 @@ cs_status launch_rope_table(const int32_t* pos, const int32_t* axis, const float
   return CS_OK;
 }
 
+// ---- split-K sums into the residual stream: x += scale * (sum of parts + bias), parts added in index order
+__global__ __launch_bounds__(256) void add_partials_kernel(float* __restrict__ x, const float* __restrict__ parts, int n_parts,
+                                                           int64_t stride, const float* __restrict__ bias,
+                                                           const float* __restrict__ scale, int64_t rows, int dim) {
+  const int cpr = dim >> 2;
+  const int64_t total = rows * cpr;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / cpr;
+    const int c = (int)(t - r * cpr);
+    float4 a = reinterpret_cast<const float4*>(parts + r * dim)[c];
+    for (int s = 1; s < n_parts; ++s) {
+      const float4 p = reinterpret_cast<const float4*>(parts + s * stride + r * dim)[c];
+      a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+    }
+    if (bias) {
+      const float4 b = reinterpret_cast<const float4*>(bias)[c];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    if (scale) {
+      const float4 g = reinterpret_cast<const float4*>(scale)[c];
+      a.x *= g.x; a.y *= g.y; a.z *= g.z; a.w *= g.w;
+    }
+    float4 v = reinterpret_cast<float4*>(x + r * dim)[c];
+    v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+    reinterpret_cast<float4*>(x + r * dim)[c] = v;
+  }
+}
+
+cs_status launch_add_partials(float* x, const float* parts, int32_t n_parts, int64_t stride, const float* bias,
+                              const float* scale, int64_t rows, int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if ((dim & 3) || n_parts < 1 || (stride & 3)) return fail(CS_ERR_UNSUPPORTED, "add_partials: dim and stride must be multiples of 4");
+  const int64_t total = rows * (dim >> 2);
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
+  hipLaunchKernelGGL(add_partials_kernel, dim3(blocks), dim3(256), 0, s, x, parts, n_parts, stride, bias, scale, rows, dim);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
 // ---- x[r,:] += table[pos[r],:]
 __global__ __launch_bounds__(256) void add_rows_kernel(float* __restrict__ x, const float* __restrict__ table,
                                                        const int32_t* __restrict__ pos, int64_t rows, int dim) {

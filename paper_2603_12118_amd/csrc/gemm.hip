@@ -237,7 +237,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
     const int rt = (i * NWAVES + wave) * 8 + lr;
     int r = n0 + rt;
     r = r < N ? r : N - 1;
-    bp[i] = g.W + (int64_t)r * K + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
+    bp[i] = g.W + (int64_t)r * g.ldw + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
   }
   const int KT = K >> 6;
   issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
@@ -525,6 +525,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 template <int BM, int BN, int WGM, int WGN, int EPI, bool LIGHT_TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
+  if (gridDim.y > 1) {   // split K (plain fp32 partial sums only): this workgroup's part of A, W and of the output
+    g.A += (int64_t)blockIdx.y * g.K;
+    g.W += (int64_t)blockIdx.y * g.K;
+    g.out = static_cast<float*>(g.out) + (int64_t)blockIdx.y * g.split_stride;
+  }
   const int M = g.M, N = g.N;
   const int tiles_n = (N + BN - 1) / BN;
   int tiles_m = (M + BM - 1) / BM;
@@ -580,7 +585,7 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   int tiles = ((g.M + BM - 1) / BM) * tiles_n;
   if (LIGHT_TAIL)   // full tile rows, then the remaining rows in 64-row tiles
     tiles = (g.M / BM) * tiles_n + ((g.M % BM + 63) / 64) * tiles_n;
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(NT), LDS, stream, g);
+  hipLaunchKernelGGL(kern, dim3(tiles, g.splits > 1 ? g.splits : 1), dim3(NT), LDS, stream, g);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -624,8 +629,14 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }
 
-cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream) {
+cs_status launch_gemm(int epilogue, const GemmArgs& g_in, hipStream_t stream) {
+  GemmArgs g = g_in;
   if (g.M <= 0 || g.N <= 0) return CS_OK;
+  if (g.ldw == 0) g.ldw = (int64_t)g.K * (g.splits > 1 ? g.splits : 1);
+  if (g.ldw < g.K || (g.ldw & 7)) return fail(CS_ERR_INVALID_ARG, "gemm: ldw must be at least K and a multiple of 8");
+  if (g.splits > 1 && (epilogue != EPI_F32 || g.bias || g.row_map || g.splits > 16 ||
+                       g.split_stride < (int64_t)g.M * g.ldo || (g.split_stride & 3)))
+    return fail(CS_ERR_UNSUPPORTED, "gemm: split K writes plain fp32 partial sums (no bias, no row map), at most 16 parts");
   if (g.K <= 0 || (g.K & 63)) return fail(CS_ERR_UNSUPPORTED, "gemm: K must be a positive multiple of 64");
   // lda < K is allowed: rows may overlap (a k=3 convolution reads three consecutive frames per row)
   if ((g.lda & 7) || (reinterpret_cast<uintptr_t>(g.A) & 15) || (reinterpret_cast<uintptr_t>(g.W) & 15))

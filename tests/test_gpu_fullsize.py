@@ -110,13 +110,20 @@ def test_c3_varlen_batch():
     check_rows("c3", out, w)
     check_forward(w, out)
     same_bits_again(enc, x, w, out, ws)
-    # batch invariance at full size: the smallest item alone gives the same rows
+    # the smallest item alone (a small batch takes other tile shapes and splits the residual GEMMs over
+    # K): its sampled rows against the checker's, and against what it gives inside the batch (both are
+    # within the embedding tolerance of the checker; between themselves they are held to the same bar)
     it = int(np.argmin(w.grid_thw.prod(1)))
     one = w.select_items([it])
     o1, _ = enc.cs_encode(dev_bf16(one.patches), one.cu_seqlens, one.grid_thw)
     torch.cuda.synchronize()
     ocu = np.concatenate([[0], np.cumsum(w.out_rows)])
-    assert (o1 - out[ocu[it]:ocu[it + 1]]).abs().max().item() <= 1e-2
+    gold = golden_items("c3")[it]
+    g1 = o1[torch.from_numpy(gold["rows"]).to(DEV)].double().cpu().numpy()
+    err1 = np.abs(g1 - gold["values"].astype(np.float64)).max()
+    print(f"c3 item {it} alone: max_abs_err={err1:.4g}", flush=True)
+    assert err1 <= MAX_ABS
+    assert (o1 - out[ocu[it]:ocu[it + 1]]).abs().max().item() <= MAX_ABS
 
 
 def same_bits_again(enc, x, w, out, ws):
