@@ -424,7 +424,10 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   }
   w.big = take(big);
   w.split_k = N <= SPLIT_K_MAX_TOKENS;
-  w.parts = take(w.split_k ? (size_t)MAX_K_PARTS * N * D * 4 : 0);
+  // partial sums of the widest split GEMM: the residual ones (N x D) or the merger's (groups x its widths)
+  size_t part = (size_t)N * D;
+  if (c.arch != CS_ARCH_AUDIO) part = std::max(part, (size_t)p.n_groups * std::max<int64_t>(e->MH_pad, c.out_hidden));
+  w.parts = take(w.split_k ? (size_t)MAX_K_PARTS * part * 4 : 0);
   w.total = off;
   return w;
 }
@@ -661,6 +664,18 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   // Small batches: partial sums over parts of K into the workspace (more workgroups, shorter K loops),
   // then one pass that adds them to x in a fixed order.
   float* parts = reinterpret_cast<float*>(ws + w.parts);
+  PendingSum pending;
+  auto take_pending = [&] {
+    const PendingSum a = pending;
+    pending = PendingSum();
+    return a;
+  };
+  // for the consumers of x that cannot add pending sums themselves
+  auto flush_pending = [&]() -> cs_status {
+    if (!pending.parts) return CS_OK;
+    const PendingSum a = take_pending();
+    return launch_add_partials(x, a.parts, a.n_parts, a.stride, a.bias, a.scale, N, (int32_t)D, stream);
+  };
   auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K) -> cs_status {
     GemmArgs g = {};
     g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D;
@@ -668,7 +683,10 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     if (S > 1) {
       g.ldw = K; g.K = (int32_t)(K / S); g.splits = S; g.split_stride = N * D; g.out = parts;
       if (cs_status st = launch_gemm(EPI_F32, g, stream)) return st;
-      return launch_add_partials(x, parts, S, N * D, e->ptr<float>(bias), scale ? e->ptr<float>(scale) : nullptr, N, (int32_t)D, stream);
+      // the sums stay pending: the normalisation that reads x next adds them on its way through
+      pending.parts = parts; pending.n_parts = S; pending.stride = N * D;
+      pending.bias = e->ptr<float>(bias); pending.scale = scale ? e->ptr<float>(scale) : nullptr;
+      return CS_OK;
     }
     g.bias = e->ptr<float>(bias); g.out = x; g.K = (int32_t)K;
     if (scale) g.col_scale = e->ptr<float>(scale);
@@ -707,8 +725,8 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   const float q_scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
   auto norm = [&](size_t gain, size_t bias) {
     StepTimer tm(e, CS_STEP_NORM, stream);
-    if (vit) return launch_rmsnorm(x, e->ptr<float>(gain), c.norm_eps, xn, N, (int32_t)D, stream);
-    return launch_layernorm(x, e->ptr<float>(gain), e->ptr<float>(bias), c.norm_eps, xn, N, (int32_t)D, stream);
+    if (vit) return launch_rmsnorm(x, e->ptr<float>(gain), c.norm_eps, xn, N, (int32_t)D, stream, take_pending());
+    return launch_layernorm(x, e->ptr<float>(gain), e->ptr<float>(bias), c.norm_eps, xn, N, (int32_t)D, stream, take_pending());
   };
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& L = e->layers[l];
@@ -754,13 +772,34 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     if (vit || cls) {
       const int64_t M = p.n_groups, G = (int64_t)c.merge * c.merge * D;
       if (vit) {
-        if (cs_status st = launch_rmsnorm_split(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, c.merge * c.merge, stream)) return st;
+        if (cs_status st = launch_rmsnorm_split(x, e->ptr<float>(e->g_m), c.norm_eps, xn, N, (int32_t)D, c.merge * c.merge, stream, take_pending())) return st;
       } else {
+        if (cs_status st = flush_pending()) return st;
         if (cs_status st = launch_layernorm_wide_split(x, e->ptr<float>(e->g_m), e->ptr<float>(e->be_m), c.norm_eps, xn, M, (int32_t)G, stream)) return st;
       }
-      if (cs_status st = gemm(EPI_GELU_SPLIT, xn, 2 * G, e->w_m1, e->b_m1, big, 2 * e->MH_pad, M, e->MH_pad, 2 * G, nullptr)) return st;
-      if (cs_status st = gemm(out_epi, big, 2 * e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, 2 * e->MH_pad, plan + p.off_out_row)) return st;
+      // small batches: both GEMMs split over K like the residual ones (a few merged rows against K = 2 * 4D)
+      auto split_gemm = [&](const bf16_t* A, int64_t K, size_t W, int64_t Nn, int S) {
+        GemmArgs g = {};
+        g.A = A; g.lda = K; g.W = e->ptr<bf16_t>(W); g.ldw = K; g.K = (int32_t)(K / S); g.splits = S;
+        g.split_stride = M * Nn; g.out = parts; g.ldo = Nn; g.M = (int32_t)M; g.N = (int32_t)Nn;
+        return launch_gemm(EPI_F32, g, stream);
+      };
+      const int S1 = w.split_k ? k_parts(M, e->MH_pad, 2 * G) : 1, S2 = w.split_k ? k_parts(M, c.out_hidden, 2 * e->MH_pad) : 1;
+      if (S1 > 1) {
+        if (cs_status st = split_gemm(xn, 2 * G, e->w_m1, e->MH_pad, S1)) return st;
+        if (cs_status st = launch_add_partials_gelu_split(big, parts, S1, M * e->MH_pad, e->ptr<float>(e->b_m1), M, e->MH_pad, stream)) return st;
+      } else {
+        if (cs_status st = gemm(EPI_GELU_SPLIT, xn, 2 * G, e->w_m1, e->b_m1, big, 2 * e->MH_pad, M, e->MH_pad, 2 * G, nullptr)) return st;
+      }
+      if (S2 > 1) {
+        if (cs_status st = split_gemm(big, 2 * e->MH_pad, e->w_m2, c.out_hidden, S2)) return st;
+        if (cs_status st = launch_add_partials_store(out_embeddings, c.out_dtype == CS_BF16, plan + p.off_out_row, parts, S2,
+                                                     M * c.out_hidden, e->ptr<float>(e->b_m2), M, c.out_hidden, stream)) return st;
+      } else {
+        if (cs_status st = gemm(out_epi, big, 2 * e->MH_pad, e->w_m2, e->b_m2, out_embeddings, c.out_hidden, M, c.out_hidden, 2 * e->MH_pad, plan + p.off_out_row)) return st;
+      }
     } else {
+      if (cs_status st = flush_pending()) return st;
       if (cs_status st = launch_pool_layernorm(x, e->ptr<float>(e->g_p), e->ptr<float>(e->be_p), c.norm_eps, xn, p.n_out, (int32_t)D, c.merge, stream)) return st;
       if (cs_status st = gemm(out_epi, xn, D, e->w_p, e->b_p, out_embeddings, c.out_hidden, p.n_out, c.out_hidden, D, nullptr)) return st;
     }

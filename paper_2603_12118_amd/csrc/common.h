@@ -94,6 +94,19 @@ __host__ __device__ inline bool lines_exclusive(const void* base, int64_t pitch_
   return ((reinterpret_cast<uintptr_t>(base) | static_cast<uintptr_t>(pitch_bytes)) & 127) == 0;
 }
 
+// GELU(z) = z Phi(z) with erfc from the five-term rational approximation of Abramowitz & Stegun
+// 7.1.26 (absolute error below 1.5e-7): erfc(x) = t (a1 + t (a2 + ... t a5)) exp(-x^2), t = 1 / (1 + p x),
+// x >= 0.  Phi(z) = erfc(|z| / sqrt 2) / 2 for z < 0 and one minus that otherwise, so the negative side
+// has no cancellation.  A dozen instructions with the hardware reciprocal and exp2 where the library
+// erff takes several times that, for every element of the audio MLP's widest epilogue.
+__device__ __forceinline__ float gelu_erf(float z) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float half_erfc = 0.5f * poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
+  return z * (z < 0.f ? half_erfc : 1.0f - half_erfc);
+}
+
 // pixels -> patch rows (elementwise.hip): up to PATCHIFY_ITEMS items [F,3,H,W] per launch, described by value
 constexpr int PATCHIFY_ITEMS = 32;
 struct PatchifyItems {
@@ -126,13 +139,23 @@ struct AttnArgs {
 cs_status launch_attention(const AttnArgs& a, hipStream_t stream);
 
 // ---- row-wise and copy kernels ----------------------------------------------------------
-cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
-                         hipStream_t s);
+// Split-K partial sums of a residual GEMM that the next normalisation adds to x on its way through:
+// x[r, n] += scale[n] * (sum over s of parts[s*stride + r*dim + n] + bias[n]), written back to x, then
+// normalised.  parts == nullptr: nothing pending.  scale may be nullptr (1).
+struct PendingSum {
+  const float* parts = nullptr;
+  int32_t n_parts = 0;
+  int64_t stride = 0;
+  const float* bias = nullptr;
+  const float* scale = nullptr;
+};
+cs_status launch_rmsnorm(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim, hipStream_t s,
+                         const PendingSum& add = PendingSum());
 // y[g, 0:group*dim) = bf16 hi parts of `group` consecutive normalised rows, y[g, group*dim : 2*group*dim) = lo parts
-cs_status launch_rmsnorm_split(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
-                               int32_t group, hipStream_t s);
-cs_status launch_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
-                           int64_t rows, int32_t dim, hipStream_t s);
+cs_status launch_rmsnorm_split(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                               int32_t group, hipStream_t s, const PendingSum& add = PendingSum());
+cs_status launch_layernorm(float* x, const float* gain, const float* bias, float eps, bf16_t* y, int64_t rows,
+                           int32_t dim, hipStream_t s, const PendingSum& add = PendingSum());
 // y[r] = layernorm(mean of `pool` consecutive rows of x)
 cs_status launch_pool_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y,
                                 int64_t out_rows, int32_t dim, int32_t pool, hipStream_t s);
@@ -151,6 +174,14 @@ cs_status launch_layernorm_wide_split(const float* x, const float* gain, const f
 // x[r, n] += scale[n] * (sum over s of parts[s*stride + r*dim + n] + bias[n]); scale / bias may be NULL (1 / 0)
 cs_status launch_add_partials(float* x, const float* parts, int32_t n_parts, int64_t stride, const float* bias,
                               const float* scale, int64_t rows, int32_t dim, hipStream_t s);
+// split-K sums of the merger's two GEMMs.  hidden: y = gelu(sum of parts + bias) written as bf16 hi at
+// out[r, n] and bf16 lo = y - hi at out[r, dim + n] (rows of 2*dim).  store: out[row_map[r], n] = sum of
+// parts + bias as fp32 or bf16 (out_bf16), rows of `dim`; row_map may be NULL, negative entries are skipped
+cs_status launch_add_partials_gelu_split(bf16_t* out, const float* parts, int32_t n_parts, int64_t stride,
+                                         const float* bias, int64_t rows, int32_t dim, hipStream_t s);
+cs_status launch_add_partials_store(void* out, int out_bf16, const int32_t* row_map, const float* parts,
+                                    int32_t n_parts, int64_t stride, const float* bias, int64_t rows, int32_t dim,
+                                    hipStream_t s);
 // x[r, :] += table[pos[r], :]
 cs_status launch_add_rows(float* x, const float* table, const int32_t* pos, int64_t rows, int32_t dim,
                           hipStream_t s);

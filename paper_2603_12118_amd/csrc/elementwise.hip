@@ -23,10 +23,10 @@ constexpr int NORM_MAX_V4 = 8;  // a wave keeps a row of up to 64*4*8 = 2048 flo
 
 // One wave per row.  MODE 0: RMSNorm.  MODE 1: LayerNorm.  POOL rows of x are averaged first.
 template <int MODE>
-__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+__global__ __launch_bounds__(256) void norm_kernel(float* __restrict__ x, const float* __restrict__ gain,
                                                    const float* __restrict__ bias, float eps,
                                                    bf16_t* __restrict__ y, int64_t rows, int dim, int pool, int split_group,
-                                                   bool wt) {
+                                                   bool wt, PendingSum add) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -44,6 +44,23 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
       if (pool > 1) {
         const float ip = 1.0f / pool;
         v[i].x *= ip; v[i].y *= ip; v[i].z *= ip; v[i].w *= ip;
+      }
+      if (add.parts) {   // pending split-K sums join the residual stream here (pool == 1)
+        float4 a = reinterpret_cast<const float4*>(add.parts + row * dim)[c];
+        for (int s = 1; s < add.n_parts; ++s) {
+          const float4 t = reinterpret_cast<const float4*>(add.parts + s * add.stride + row * dim)[c];
+          a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        if (add.bias) {
+          const float4 t = reinterpret_cast<const float4*>(add.bias)[c];
+          a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        if (add.scale) {
+          const float4 t = reinterpret_cast<const float4*>(add.scale)[c];
+          a.x *= t.x; a.y *= t.y; a.z *= t.z; a.w *= t.w;
+        }
+        v[i].x += a.x; v[i].y += a.y; v[i].z += a.z; v[i].w += a.w;
+        reinterpret_cast<float4*>(x + row * dim)[c] = v[i];
       }
     }
   }
@@ -97,33 +114,33 @@ static cs_status norm_check(int64_t rows, int dim) {
   return CS_OK;
 }
 
-cs_status launch_rmsnorm(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
-                         hipStream_t s) {
+cs_status launch_rmsnorm(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim, hipStream_t s,
+                         const PendingSum& add) {
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
-                     rows, dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2));
+                     rows, dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2), add);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
 
-cs_status launch_rmsnorm_split(const float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
-                               int32_t group, hipStream_t s) {
+cs_status launch_rmsnorm_split(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
+                               int32_t group, hipStream_t s, const PendingSum& add) {
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   if (group < 1 || rows % group) return fail(CS_ERR_INVALID_ARG, "rmsnorm_split: rows must be a multiple of the group");
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
-                     rows, dim, 1, group, lines_exclusive(y, (int64_t)dim * 2));
+                     rows, dim, 1, group, lines_exclusive(y, (int64_t)dim * 2), add);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
 
-cs_status launch_layernorm(const float* x, const float* gain, const float* bias, float eps, bf16_t* y, int64_t rows,
-                           int32_t dim, hipStream_t s) {
+cs_status launch_layernorm(float* x, const float* gain, const float* bias, float eps, bf16_t* y, int64_t rows,
+                           int32_t dim, hipStream_t s, const PendingSum& add) {
   if (rows <= 0) return CS_OK;
   if (cs_status st = norm_check(rows, dim)) return st;
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y, rows,
-                     dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2));
+                     dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2), add);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -133,8 +150,8 @@ cs_status launch_pool_layernorm(const float* x, const float* gain, const float* 
   if (out_rows <= 0) return CS_OK;
   if (cs_status st = norm_check(out_rows, dim)) return st;
   if (pool < 1) return fail(CS_ERR_INVALID_ARG, "pool_layernorm: pool < 1");
-  hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y,
-                     out_rows, dim, pool, 0, lines_exclusive(y, (int64_t)dim * 2));
+  hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, const_cast<float*>(x), gain, bias,
+                     eps, y, out_rows, dim, pool, 0, lines_exclusive(y, (int64_t)dim * 2), PendingSum());
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
@@ -240,6 +257,76 @@ cs_status launch_add_partials(float* x, const float* parts, int32_t n_parts, int
   const int64_t total = rows * (dim >> 2);
   const unsigned blocks = (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
   hipLaunchKernelGGL(add_partials_kernel, dim3(blocks), dim3(256), 0, s, x, parts, n_parts, stride, bias, scale, rows, dim);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+// MODE 0: gelu, bf16 hi | lo.  MODE 1: plain store through the row map, fp32 or bf16.
+template <int MODE>
+__global__ __launch_bounds__(256) void add_partials_out_kernel(void* __restrict__ out, int out_bf16,
+                                                               const int32_t* __restrict__ row_map,
+                                                               const float* __restrict__ parts, int n_parts, int64_t stride,
+                                                               const float* __restrict__ bias, int64_t rows, int dim) {
+  const int cpr = dim >> 2;
+  const int64_t total = rows * cpr;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t r = t / cpr;
+    const int c = (int)(t - r * cpr);
+    float4 a = reinterpret_cast<const float4*>(parts + r * dim)[c];
+    for (int s = 1; s < n_parts; ++s) {
+      const float4 p = reinterpret_cast<const float4*>(parts + s * stride + r * dim)[c];
+      a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+    }
+    if (bias) {
+      const float4 b = reinterpret_cast<const float4*>(bias)[c];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    if (MODE == 0) {
+      const float y0 = gelu_erf(a.x), y1 = gelu_erf(a.y), y2 = gelu_erf(a.z), y3 = gelu_erf(a.w);
+      uint2 hi, lo;
+      hi.x = pack2_e(y0, y1);
+      hi.y = pack2_e(y2, y3);
+      lo.x = pack2_e(y0 - __uint_as_float(hi.x << 16), y1 - __uint_as_float(hi.x & 0xFFFF0000u));
+      lo.y = pack2_e(y2 - __uint_as_float(hi.y << 16), y3 - __uint_as_float(hi.y & 0xFFFF0000u));
+      bf16_t* dst = static_cast<bf16_t*>(out) + r * (2 * (int64_t)dim);
+      reinterpret_cast<uint2*>(dst)[c] = hi;
+      reinterpret_cast<uint2*>(dst + dim)[c] = lo;
+    } else {
+      const int64_t row = row_map ? row_map[r] : r;
+      if (row < 0) continue;
+      if (out_bf16) {
+        uint2 pk;
+        pk.x = pack2_e(a.x, a.y);
+        pk.y = pack2_e(a.z, a.w);
+        reinterpret_cast<uint2*>(static_cast<bf16_t*>(out) + row * dim)[c] = pk;
+      } else {
+        reinterpret_cast<float4*>(static_cast<float*>(out) + row * dim)[c] = a;
+      }
+    }
+  }
+}
+
+static unsigned partials_blocks(int64_t rows, int dim) {
+  const int64_t total = rows * (dim >> 2);
+  return (unsigned)((total + 255) / 256 < 65536 * 16 ? (total + 255) / 256 : 65536 * 16);
+}
+
+cs_status launch_add_partials_gelu_split(bf16_t* out, const float* parts, int32_t n_parts, int64_t stride,
+                                         const float* bias, int64_t rows, int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if ((dim & 3) || n_parts < 1 || (stride & 3)) return fail(CS_ERR_UNSUPPORTED, "add_partials: dim and stride must be multiples of 4");
+  hipLaunchKernelGGL(add_partials_out_kernel<0>, dim3(partials_blocks(rows, dim)), dim3(256), 0, s, out, 1, nullptr, parts,
+                     n_parts, stride, bias, rows, dim);
+  CS_HIP(hipGetLastError());
+  return CS_OK;
+}
+
+cs_status launch_add_partials_store(void* out, int out_bf16, const int32_t* row_map, const float* parts, int32_t n_parts,
+                                    int64_t stride, const float* bias, int64_t rows, int32_t dim, hipStream_t s) {
+  if (rows <= 0) return CS_OK;
+  if ((dim & 3) || n_parts < 1 || (stride & 3)) return fail(CS_ERR_UNSUPPORTED, "add_partials: dim and stride must be multiples of 4");
+  hipLaunchKernelGGL(add_partials_out_kernel<1>, dim3(partials_blocks(rows, dim)), dim3(256), 0, s, out, out_bf16, row_map,
+                     parts, n_parts, stride, bias, rows, dim);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }

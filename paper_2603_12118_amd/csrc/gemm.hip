@@ -36,18 +36,6 @@ __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
   const bf16x4 h = __builtin_convertvector(v, bf16x4);
   return __builtin_bit_cast(u32x2, h);
 }
-// GELU(z) = z Phi(z) with erfc from the five-term rational approximation of Abramowitz & Stegun
-// 7.1.26 (absolute error below 1.5e-7): erfc(x) = t (a1 + t (a2 + ... t a5)) exp(-x^2), t = 1 / (1 + p x),
-// x >= 0.  Phi(z) = erfc(|z| / sqrt 2) / 2 for z < 0 and one minus that otherwise, so the negative side
-// has no cancellation.  A dozen instructions with the hardware reciprocal and exp2 where the library
-// erff takes several times that, for every element of the audio MLP's widest epilogue.
-__device__ __forceinline__ float gelu_erf(float z) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float half_erfc = 0.5f * poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
-  return z * (z < 0.f ? half_erfc : 1.0f - half_erfc);
-}
 // z * sigmoid(z) with the hardware exp2 and reciprocal (1 ulp each): five instructions, where the
 // IEEE division costs a dozen, and this runs for every element of the widest GEMM's epilogue
 __device__ __forceinline__ float silu_f(float z) {
