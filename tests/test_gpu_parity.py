@@ -383,6 +383,30 @@ def test_outputs_that_do_not_start_on_a_128_byte_line():
     assert np.abs(out.float().cpu().numpy() - O.linear(A, W)).max() <= 2 ** -8 * 12 + 1e-6
 
 
+@pytest.mark.parametrize("tower", ["vit", "audio", "vit_cls"])
+def test_encode_with_workspace_and_output_16_bytes_into_an_allocation(tower):
+    """Every buffer of the path then starts 16 bytes past a 128-byte line, so every kernel takes its plain
+    stores instead of the write-through ones: the embeddings must come out with the same bits."""
+    if tower == "vit":
+        w = wl.small_vit(n_layers=2)
+    elif tower == "audio":
+        w = wl.audio_workload("small_audio", wl.audio_config(n_layers=2), n_clips=2, n_frames=400, seq_len=256)
+    else:
+        w = wl.small_cls(n_layers=2)
+    enc = B.Encoder(w.cfg, w.weights)
+    x = dev_input(w)
+    n_out, ws_bytes = enc.cs_encoder_query(w.cu_seqlens, w.grid_thw)
+    out, _ = enc.cs_encode(x, w.cu_seqlens, w.grid_thw)
+    raw_ws = torch.empty(ws_bytes + 64, dtype=torch.uint8, device=DEV)
+    raw_out = torch.empty(n_out * w.cfg.out_hidden * 4 + 64, dtype=torch.uint8, device=DEV)
+    ws2 = raw_ws[16:16 + ws_bytes]
+    out2 = raw_out[16:16 + n_out * w.cfg.out_hidden * 4].view(torch.float32).view(n_out, w.cfg.out_hidden)
+    assert ws2.data_ptr() % 128 == 16 and out2.data_ptr() % 128 == 16 and out.data_ptr() % 128 == 0
+    enc.cs_encode(x, w.cu_seqlens, w.grid_thw, out=out2, workspace=ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
 # ------------------------------------------------------------------ class-token tower
 @pytest.mark.parametrize("tile,n_tiles", [((6, 10), 3), ((2, 2), 1), ((16, 18), 2), ((32, 32), 1)])
 def test_encode_class_token_tower(tile, n_tiles):
