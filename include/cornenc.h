@@ -30,6 +30,10 @@
  *    host before anything is enqueued.
  *  - The caller owns every buffer it passes in, the workspace included.  The library
  *    owns its repacked copy of the weights and small host staging buffers.
+ *  - Threads: calls on different encoders (and the stateless calls) may run concurrently;
+ *    calls on one cs_encoder must not overlap on the host (cs_encode keeps per-encoder
+ *    staging state), though the work of successive calls may overlap on the GPU if they
+ *    use different workspaces and streams.
  */
 #ifndef CORNENC_H
 #define CORNENC_H
