@@ -407,6 +407,33 @@ def test_encode_with_workspace_and_output_16_bytes_into_an_allocation(tower):
     assert torch.equal(out, out2)
 
 
+def test_calls_of_one_encoder_overlapping_on_two_streams():
+    """Six calls of one encoder alternating between two streams, each stream with its own workspace and
+    outputs, nothing synchronised in between (the per-batch index tables go through two pinned
+    staging slots that are reused while earlier calls are still running): every result has the bits
+    of the same batch run alone."""
+    wa = wl.small_vit(n_layers=2)
+    wb = wl.small_vit(sizes_px=((112, 56), (56, 280)), n_layers=2)
+    enc = B.Encoder(wa.cfg, wa.weights)
+    xa, xb = dev_input(wa), dev_input(wb)
+    alone_a, _ = enc.cs_encode(xa, wa.cu_seqlens, wa.grid_thw)
+    alone_b, _ = enc.cs_encode(xb, wb.cu_seqlens, wb.grid_thw)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    # all memory is allocated before the first call, so that nothing is handed out again while a call still uses it
+    need = max(enc.cs_encoder_query(w.cu_seqlens, w.grid_thw)[1] for w in (wa, wb))
+    ws = [torch.empty(need, dtype=torch.uint8, device=DEV) for _ in range(2)]
+    plan = [(wa, xa, alone_a) if i % 3 != 1 else (wb, xb, alone_b) for i in range(6)]
+    outs = [torch.empty_like(want) for (_, _, want) in plan]
+    torch.cuda.synchronize()
+    for i, (w, x, _) in enumerate(plan):
+        enc.cs_encode(x, w.cu_seqlens, w.grid_thw, out=outs[i], workspace=ws[i % 2], stream=streams[i % 2])
+    torch.cuda.synchronize()
+    outs = [(o, want) for o, (_, _, want) in zip(outs, plan)]
+    for i, (o, want) in enumerate(outs):
+        assert torch.equal(o, want), f"call {i}"
+
+
 # ------------------------------------------------------------------ class-token tower
 @pytest.mark.parametrize("tile,n_tiles", [((6, 10), 3), ((2, 2), 1), ((16, 18), 2), ((32, 32), 1)])
 def test_encode_class_token_tower(tile, n_tiles):
