@@ -2,12 +2,12 @@
  * cornenc -- the encoder task and the embedding hand-off of a disaggregated
  * multimodal serving system, as a C-ABI library for one MI355X (gfx950).
  *
- * The paper splits a multimodal LLM at the encoder boundary (Sec. 3.1 "Model
+ * The paper splits a multimodal LLM at the encoder boundary (Sec. 2.2 "Model
  * Fission", Listing 1): an encoder task, run by its own executor on its own GPU
- * (Sec. 2 "Data Plane"), turns every multimodal item of a request into one
+ * (Sec. 2.1 "Data Plane"), turns every multimodal item of a request into one
  * embedding tensor; the tensors are appended to the request in item order; the
  * LLM task, created to receive embeddings, does not run an encoder and takes the
- * tensors forwarded to it (Sec. 3.1 "Data Forwarding").  This library is the GPU
+ * tensors forwarded to it (Sec. 2.2 "Data Forwarding").  This library is the GPU
  * compute on both sides of that boundary:
  *
  *   cs_encode              the encoder task on one packed, variable-length batch
@@ -26,8 +26,12 @@
  *  - "dev" pointers are device memory of the current HIP device, "host" pointers
  *    are ordinary host memory.  All dev pointers must be 16-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The two
- *    hot calls only enqueue work on it and return; arguments are validated on the
- *    host before anything is enqueued.
+ *    hot calls enqueue work on it and return; arguments are validated on the host
+ *    before anything is enqueued.  cs_encode waits on the host in two cases only: a
+ *    third call while the copy of the index tables of the call before the previous
+ *    one has not started yet (two pinned staging slots are used in turn), and a batch
+ *    whose index tables outgrow those slots (1 MiB each from create on, about 40 000
+ *    tokens), which re-allocates them and so synchronises the device once.
  *  - The caller owns every buffer it passes in, the workspace included.  The library
  *    owns its repacked copy of the weights and small host staging buffers.
  *  - Threads: calls on different encoders (and the stateless calls) may run concurrently;
@@ -54,7 +58,8 @@ typedef enum {
   CS_ERR_UNSUPPORTED = 5, /* a configuration the kernels are not built for          */
   CS_ERR_HIP = 6,         /* a HIP runtime call failed (text in cs_last_error)      */
   CS_ERR_MISSING_WEIGHT = 7,
-  CS_ERR_BUSY = 8         /* cs_channel_acquire: every slot is in use; try again later */
+  CS_ERR_BUSY = 8,        /* cs_channel_acquire: every slot is in use; try again later */
+  CS_ERR_NO_MEMORY = 9    /* a host allocation inside the library failed               */
 } cs_status;
 
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
@@ -142,11 +147,14 @@ cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* we
 void cs_encoder_destroy(cs_encoder* enc);
 
 /* Host-only: validates a batch description and reports how many embedding rows cs_encode
- * will write and how large a workspace it needs.  cu_seqlens, grid_thw as for cs_encode. */
+ * will write and how large a workspace it needs.  cu_seqlens, grid_thw as for cs_encode.
+ * The plan of a batch (token permutation, attention work lists, output rows) depends only on
+ * its description; the encoder keeps the plans of the last 8 distinct descriptions, so a
+ * query followed by the encode, or a serving loop over a few image sizes, plans once. */
 cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw,
                            int32_t n_items, int64_t* n_out_rows, size_t* workspace_bytes);
 
-/* The encoder task (Sec. 2 "Data Plane": the executor for image, video and audio encoders;
+/* The encoder task (Sec. 2.1 "Data Plane": the executor for image, video and audio encoders;
  * Listing 1: one embedding tensor per multimodal item, in item order).
  *
  *  patches         dev  [N, patch_dim], config.dtype.  vit: the patches of all items packed
@@ -155,12 +163,12 @@ cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, con
  *                       frame-major (row = frame, column = mel bin).
  *  cu_seqlens      host [n_items+1], cu_seqlens[0] = 0, item i owns rows [cu[i], cu[i+1]).
  *  grid_thw        host [n_items,3] = (t, h, w) in patches, h and w multiples of `merge`,
- *                       t*h*w == cu[i+1]-cu[i].  audio: (1, 1, frames), frames a multiple of 4.
+ *                       t*h*w == cu[i+1]-cu[i].  audio: (1, 1, frames), frames a multiple of 8 and of 2*merge.
  *                       vit_cls: an item is one tile, (1, h, w) with 1 + h*w == rows of pos_embed.
  *  out_embeddings  dev  [M, out_hidden], config.out_dtype.  vit: item i yields t*(h/2)*(w/2) rows
  *                       in raster order of the merged grid (vit_cls: (h/2)*(w/2) rows per tile, group
  *                       (R, C) = patches (2R,2C), (2R,2C+1), (2R+1,2C), (2R+1,2C+1) in that order; the
- *                       class token yields no row); audio: frames/4 rows; items in input
+ *                       class token yields no row); audio: frames/(2*merge) rows (the stride-2 convolution, then `merge` frames pooled); items in input
  *                       order.  M = sum over items (cs_encoder_query reports it).
  *  workspace       dev, at least the size cs_encoder_query reports for this batch; contents
  *                       are scratch.  Two calls that overlap in time need two workspaces.
@@ -171,7 +179,11 @@ cs_status cs_encode(cs_encoder* enc, const void* patches, const int32_t* cu_seql
                     int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
                     void* stream);
 
-/* The hand-off on the consumer side (Sec. 3.1 "Data Forwarding": the receiver copies the
+/* Host-only: how often a batch description was found in (hits) or added to (misses) the encoder's
+ * plan cache since create, over cs_encoder_query and cs_encode.  Either may be NULL. */
+cs_status cs_encoder_plan_cache_stats(const cs_encoder* enc, int64_t* hits, int64_t* misses);
+
+/* The hand-off on the consumer side (Sec. 2.2 "Data Forwarding": the receiver copies the
  * forwarded tensor into its GPU memory; Listing 1: the LLM task takes embeddings instead of
  * encoding):  dst_seq[placeholder_index[i], :] = src[i, :]  as a copy of storage words.
  *
@@ -190,8 +202,8 @@ cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_inde
 /* cs_channel: the hand-off as a channel between an encoder task (producer) and an LLM task
  * (consumer) that run on two streams of one process on one GPU.  In the paper a producer's tensor
  * is put into a shared buffer, the consumer is told its address, copies it into its own memory, and
- * executors wait for tensors that have not arrived yet (Sec. 3.1 "Data Forwarding", Sec. 4.3
- * "Sidecar").  Here the shared buffer is a pool of equally sized slots in device memory, the
+ * executors wait for tensors that have not arrived yet (Sec. 2.2 "Data Forwarding", Sec. 2.1
+ * "Request Lifecycle"; cost in Sec. 3 "Sidecar Overhead").  Here the shared buffer is a pool of equally sized slots in device memory, the
  * notification is the slot number with its description (rows, width, dtype), "arrived" is a HIP
  * event, and the consumer's copy is the placement itself (the scatter of cs_forward_embeddings
  * reading the slot), so rows move once and never leave HBM.  No call blocks the host:
@@ -270,7 +282,7 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
                               int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream);
 
 /* Timing of one step of the encoder task with HIP events on the caller's stream (measurement
- * aid; Sec. 2 mentions tracing only in passing).  After cs_encoder_time_step(enc, step), every
+ * aid; Sec. 1 mentions tracing only in passing).  After cs_encoder_time_step(enc, step), every
  * cs_encode records an event pair around each launch of that step; cs_encoder_read_timing waits
  * for the recorded events, returns the summed elapsed milliseconds and the number of launches
  * since the last read, and clears them.  step = CS_STEP_NONE switches recording off. */
@@ -294,7 +306,7 @@ cs_status cs_encoder_time_every(cs_encoder* enc, int32_t every);
 cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* launches);
 
 /* cs_pack_batch: host-only choice of the items that go into the next packed cs_encode call of an
- * encoder shared by several apps (Sec. 3.1 "Component Sharing": equivalent encoder tasks share one
+ * encoder shared by several apps (Sec. 2.2 "Component Sharing": equivalent encoder tasks share one
  * executor, so items of different requests and models queue at the same encoder).  The paper
  * names no policy; this one is first-fit in arrival order under a row budget:
  *   - pending items are given oldest first, item i with rows_i = t*h*w input rows (grid_thw as
@@ -313,8 +325,8 @@ cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_
                         int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid);
 
 /* cs_patchify: pixels -> the patch rows cs_encode takes, for callers that hold decoded frames
- * (the step in front of the encoder task; the paper leaves preprocessing to the model's own
- * processor, Sec. 3.1).  No resizing: sides must already be multiples of the patch size.
+ * (the step in front of the encoder task; the paper says nothing of preprocessing: in Listing 1 the
+ * encoder task is handed the request's multimodal data as it is).  No resizing: sides must already be multiples of the patch size.
  *  frames      dev, items back to back, item i = [F_i, 3, H_i, W_i] of in_dtype (CS_F32 or CS_BF16),
  *              16-byte aligned; every item must start 16-byte aligned (it does when H*W is a multiple of 8)
  *  frame_dims  HOST int32 [n_items,3] = (F, H, W) in pixels; H, W multiples of patch; F == 1 or a

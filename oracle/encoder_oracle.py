@@ -6,7 +6,7 @@ raster token order, with dense boolean attention masks and no tiling, fusion or
 reordering.  It shares no code with the GPU path and imports nothing from it;
 only tests, the smoke check and the benchmark's CPU-baseline leg may call it.
 
-What the paper fixes (Sec. 2 "Data Plane"; Sec. 3.1 "Model Fission", Listing 1)
+What the paper fixes (Sec. 2.1 "Data Plane"; Sec. 2.2 "Model Fission", Listing 1)
 is the boundary: an encoder task turns each multimodal item of a request into
 one embedding tensor, the tensors are appended in item order, and an LLM task
 created to receive embeddings places them into its input instead of running an
@@ -337,8 +337,9 @@ def patchify(frames: np.ndarray, temporal_patch: int, patch: int = 14) -> Tuple[
     Patch (t, r, c) is row (t*h + r)*w + c; inside the row, element
     ((ch*tp + tt)*patch + py)*patch + px is pixel frames[t*tp + tt, ch, r*patch + py, c*patch + px].
     An item with a single frame shows that frame in every temporal slot.  Values are copied as they
-    are (no arithmetic); the dtype of `frames` is kept.  Reading: the paper leaves preprocessing to
-    each model's own processor (Sec. 3.1); this is the layout such vision towers take."""
+    are (no arithmetic); the dtype of `frames` is kept.  Reading: the paper says nothing
+    of preprocessing (in Listing 1 the encoder task is handed the request's multimodal data as it
+    is); this is the layout such vision towers take."""
     F, C, H, W = frames.shape
     tp = temporal_patch
     assert C == 3 and H % patch == 0 and W % patch == 0 and (F == 1 or F % tp == 0)
@@ -380,7 +381,7 @@ def pack_batch(rows: Sequence[int], row_budget: int, max_items: int) -> list:
     """First-fit in arrival order: `rows` lists the pending items' input-row counts oldest first.
     The oldest item is always taken; every later one is taken when the total stays within the
     budget and fewer than max_items are taken.  Returns the taken indices.  (The paper shares one
-    encoder between apps, Sec. 3.1 "Component Sharing", and names no batching policy; first-fit is
+    encoder between apps, Sec. 2.2 "Component Sharing", and names no batching policy; first-fit is
     the policy chosen here.)"""
     taken, total = [], 0
     for i, r in enumerate(rows):
@@ -409,7 +410,7 @@ def forward_embeddings(src: np.ndarray, placeholder_index: np.ndarray, dst: np.n
 
 class ChannelModel:
     """The hand-off channel as a sequential program: a pool of equally sized slots, each FREE,
-    WRITING or READY (Sec. 3.1 "Data Forwarding", Sec. 4.3: a producer puts its tensor in a shared
+    WRITING or READY (Sec. 2.2 "Data Forwarding": a producer puts its tensor in a shared
     buffer, tells the consumer where it is, the consumer places it).  Every call happens at once
     and in call order; whatever overlap an implementation allows must give these results.
     Calls return a status word: "ok", "busy" (no free slot), "workspace" (tensor larger than a

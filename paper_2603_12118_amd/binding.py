@@ -19,7 +19,7 @@ CS_F32, CS_BF16 = 0, 1
 CS_ARCH_VIT, CS_ARCH_AUDIO, CS_ARCH_VIT_CLS = 0, 1, 2
 CS_ORDER_RASTER, CS_ORDER_MERGE_MAJOR = 0, 1
 CS_SLOT_FREE, CS_SLOT_WRITING, CS_SLOT_READY = 0, 1, 2
-CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY = 1, 2, 3, 5, 8
+CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY, CS_ERR_NO_MEMORY = 1, 2, 3, 5, 8, 9
 STEPS = {"front": 1, "norm": 2, "qkv": 3, "attn_window": 4, "attn_full": 5, "proj": 6, "mlp_up": 7, "mlp_down": 8,
          "back": 9}
 
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.cs_encoder_destroy.restype = None
         L.cs_encoder_query.argtypes = [vp, i32p, i32p, C.c_int32, C.POINTER(i64), C.POINTER(C.c_size_t)]
         L.cs_encode.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.cs_encoder_plan_cache_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
         L.cs_forward_embeddings.argtypes = [vp, vp, vp, i64, i64, C.c_int32, C.c_int32, vp, vp]
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
         L.cs_linear_bf16.argtypes = [vp, i64, vp, vp, vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
@@ -80,7 +81,8 @@ def lib() -> C.CDLL:
         L.cs_status_string.argtypes = [C.c_int]
         L.cs_status_string.restype = C.c_char_p
         L.cs_last_error.restype = C.c_char_p
-        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_forward_embeddings", "cs_plan_tokens",
+        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encoder_plan_cache_stats",
+                  "cs_forward_embeddings", "cs_plan_tokens",
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
                   "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
                   "cs_channel_acquire", "cs_channel_publish", "cs_channel_forward", "cs_channel_release",
@@ -195,6 +197,12 @@ class Encoder:
         _check(lib().cs_encode(self._h, patches.data_ptr(), _i32p(cu), _i32p(g), g.shape[0], out.data_ptr(),
                                workspace.data_ptr(), workspace.numel(), _stream(stream)))
         return out, workspace
+
+
+    def cs_encoder_plan_cache_stats(self):
+        hits, misses = C.c_int64(), C.c_int64()
+        _check(lib().cs_encoder_plan_cache_stats(self._h, C.byref(hits), C.byref(misses)))
+        return hits.value, misses.value
 
 
 def cs_plan_tokens(cfg, cu_seqlens, grid_thw):

@@ -7,6 +7,8 @@
 #include <algorithm>
 #include <limits>
 #include <map>
+#include <mutex>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -86,6 +88,16 @@ struct cs_encoder {
   int pe_positions = 0;
   size_t b_pe = 0, be_m = 0, pos_tab = 0;    // class-token tower: patch-embed bias, projector norm bias, position table
   int n_positions = 0;                       // rows of its position table (1 + patches per tile); row n_positions = class token + row 0
+  // plans of the batch shapes seen last (key: n_items, cu_seqlens, grid_thw), newest use = largest stamp
+  struct CachedPlan {
+    std::vector<int32_t> key;
+    cs::BatchPlan plan;
+    uint64_t stamp = 0;
+  };
+  mutable std::mutex plan_mu;
+  mutable std::vector<CachedPlan> plans;
+  mutable uint64_t plan_clock = 0;
+  mutable uint64_t plan_hits = 0, plan_misses = 0;
   // pinned staging for the per-batch index tables, two slots used in turn
   void* stage[2] = {nullptr, nullptr};
   size_t stage_cap[2] = {0, 0};
@@ -455,7 +467,7 @@ struct StepTimer {
   }
 };
 
-static cs_status make_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items, BatchPlan& p) {
+static cs_status build_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items, BatchPlan& p) {
   if (e->cfg.arch == CS_ARCH_VIT) return build_vit_plan(e->cfg, cu, grid, n_items, p);
   if (e->cfg.arch == CS_ARCH_VIT_CLS) return build_cls_plan(e->cfg, e->n_positions, cu, grid, n_items, p);
   cs_status st = build_audio_plan(e->cfg, cu, grid, n_items, p);
@@ -464,6 +476,64 @@ static cs_status make_plan(const cs_encoder* e, const int32_t* cu, const int32_t
     if (grid[3 * i + 2] / 2 > e->pe_positions) return fail(CS_ERR_UNSUPPORTED, "audio clip longer than the position table");
   return CS_OK;
 }
+
+// The plan of a batch depends only on its description, and a serving loop sees the same few
+// descriptions again and again (one image size, one clip length): the last PLAN_CACHE_ENTRIES distinct
+// ones are kept per encoder.  The returned pointer stays valid until the next call on this encoder.
+constexpr size_t PLAN_CACHE_ENTRIES = 8;
+static cs_status get_plan(const cs_encoder* e, const int32_t* cu, const int32_t* grid, int32_t n_items,
+                          const BatchPlan** out) {
+  if (!cu || !grid) return fail(CS_ERR_INVALID_ARG, "cu_seqlens / grid_thw is NULL");
+  if (n_items <= 0) return fail(CS_ERR_INVALID_ARG, "n_items must be positive");
+  std::lock_guard<std::mutex> lock(e->plan_mu);
+  for (cs_encoder::CachedPlan& c : e->plans) {
+    if ((int64_t)c.key.size() != 4 * (int64_t)n_items + 2 || c.key[0] != n_items) continue;
+    if (memcmp(c.key.data() + 1, cu, ((size_t)n_items + 1) * 4) != 0) continue;
+    if (memcmp(c.key.data() + n_items + 2, grid, (size_t)n_items * 12) != 0) continue;
+    c.stamp = ++e->plan_clock;
+    ++e->plan_hits;
+    *out = &c.plan;
+    return CS_OK;
+  }
+  BatchPlan p;
+  if (cs_status st = build_plan(e, cu, grid, n_items, p)) return st;
+  ++e->plan_misses;
+  cs_encoder::CachedPlan* slot = nullptr;
+  if (e->plans.size() < PLAN_CACHE_ENTRIES) {
+    e->plans.emplace_back();
+    slot = &e->plans.back();
+  } else {
+    slot = &e->plans[0];
+    for (cs_encoder::CachedPlan& c : e->plans)
+      if (c.stamp < slot->stamp) slot = &c;
+  }
+  slot->key.resize(4 * (size_t)n_items + 2);
+  slot->key[0] = n_items;
+  memcpy(slot->key.data() + 1, cu, ((size_t)n_items + 1) * 4);
+  memcpy(slot->key.data() + n_items + 2, grid, (size_t)n_items * 12);
+  slot->plan = std::move(p);
+  slot->stamp = ++e->plan_clock;
+  *out = &slot->plan;
+  return CS_OK;
+}
+
+// No exception may cross the C boundary: host allocations (vectors, strings, `new`) can throw.
+template <class F>
+static cs_status guarded(const char* who, F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(CS_ERR_NO_MEMORY, std::string(who) + ": out of host memory");
+  } catch (const std::exception& ex) {
+    return fail(CS_ERR_INVALID_ARG, std::string(who) + ": " + ex.what());
+  } catch (...) {
+    return fail(CS_ERR_INVALID_ARG, std::string(who) + ": unknown exception");
+  }
+}
+
+// What a pinned staging slot holds from create on: enough for the index tables of some 40 000 tokens
+// (the tables take about 24 bytes per token).  Larger batches grow the slot in cs_encode, which blocks.
+constexpr size_t STAGE_BYTES_AT_CREATE = (size_t)1 << 20;
 
 }  // namespace cs
 
@@ -480,14 +550,15 @@ const char* cs_status_string(cs_status s) {
     case CS_ERR_HIP: return "HIP runtime error";
     case CS_ERR_MISSING_WEIGHT: return "missing weight";
     case CS_ERR_BUSY: return "busy";
+    case CS_ERR_NO_MEMORY: return "out of host memory";
   }
   return "unknown status";
 }
 
 const char* cs_last_error(void) { return g_last_error.c_str(); }
 
-cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* weights, int32_t n_weights,
-                            cs_encoder** out_encoder) {
+static cs_status encoder_create(const cs_encoder_config* config, const cs_tensor* weights, int32_t n_weights,
+                                cs_encoder** out_encoder) {
   if (!config || !out_encoder || (!weights && n_weights > 0) || n_weights < 0)
     return fail(CS_ERR_INVALID_ARG, "cs_encoder_create: NULL argument");
   *out_encoder = nullptr;
@@ -519,6 +590,10 @@ cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* we
     if (he == hipSuccess) he = hipMalloc(reinterpret_cast<void**>(&e->dev), A.host.size());
     if (he == hipSuccess) he = hipMemcpy(e->dev, A.host.data(), A.host.size(), hipMemcpyHostToDevice);
     for (int s = 0; s < 2 && he == hipSuccess; ++s) he = hipEventCreateWithFlags(&e->stage_ev[s], hipEventDisableTiming);
+    for (int s = 0; s < 2 && he == hipSuccess; ++s) {
+      he = hipHostMalloc(&e->stage[s], STAGE_BYTES_AT_CREATE, hipHostMallocDefault);
+      if (he == hipSuccess) e->stage_cap[s] = STAGE_BYTES_AT_CREATE;
+    }
     if (he != hipSuccess) st = fail(CS_ERR_HIP, std::string("cs_encoder_create: ") + hipGetErrorString(he));
     e->dev_bytes = A.host.size();
   }
@@ -528,6 +603,11 @@ cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* we
   }
   *out_encoder = e;
   return CS_OK;
+}
+
+cs_status cs_encoder_create(const cs_encoder_config* config, const cs_tensor* weights, int32_t n_weights,
+                            cs_encoder** out_encoder) {
+  return guarded("cs_encoder_create", [&] { return encoder_create(config, weights, n_weights, out_encoder); });
 }
 
 void cs_encoder_destroy(cs_encoder* e) {
@@ -573,16 +653,26 @@ cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* lau
 cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw, int32_t n_items,
                            int64_t* n_out_rows, size_t* workspace_bytes) {
   if (!enc) return fail(CS_ERR_INVALID_ARG, "cs_encoder_query: NULL encoder");
-  BatchPlan p;
-  if (cs_status st = make_plan(enc, cu_seqlens, grid_thw, n_items, p)) return st;
-  if (n_out_rows) *n_out_rows = p.n_out;
-  if (workspace_bytes) *workspace_bytes = layout_workspace(enc, p).total;
+  return guarded("cs_encoder_query", [&]() -> cs_status {
+    const BatchPlan* p = nullptr;
+    if (cs_status st = get_plan(enc, cu_seqlens, grid_thw, n_items, &p)) return st;
+    if (n_out_rows) *n_out_rows = p->n_out;
+    if (workspace_bytes) *workspace_bytes = layout_workspace(enc, *p).total;
+    return CS_OK;
+  });
+}
+
+cs_status cs_encoder_plan_cache_stats(const cs_encoder* enc, int64_t* hits, int64_t* misses) {
+  if (!enc) return fail(CS_ERR_INVALID_ARG, "cs_encoder_plan_cache_stats: NULL encoder");
+  std::lock_guard<std::mutex> lock(enc->plan_mu);
+  if (hits) *hits = (int64_t)enc->plan_hits;
+  if (misses) *misses = (int64_t)enc->plan_misses;
   return CS_OK;
 }
 
-cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
-                         int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
-                         int32_t win_cu_capacity, int32_t* n_windows) {
+static cs_status plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                             int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
+                             int32_t win_cu_capacity, int32_t* n_windows) {
   if (!config) return fail(CS_ERR_INVALID_ARG, "cs_plan_tokens: NULL config");
   if (cs_status st = check_config(*config)) return st;
   if (config->arch == CS_ARCH_AUDIO) return fail(CS_ERR_UNSUPPORTED, "cs_plan_tokens: vision encoders only");
@@ -607,20 +697,34 @@ cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seql
   return CS_OK;
 }
 
-cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
-                    int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes, void* stream_) {
-  if (!e || !patches || !out_embeddings || !workspace) return fail(CS_ERR_INVALID_ARG, "cs_encode: NULL argument");
+cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                         int32_t n_items, int32_t* src_row, int32_t* out_row, int32_t* win_cu,
+                         int32_t win_cu_capacity, int32_t* n_windows) {
+  return guarded("cs_plan_tokens", [&] {
+    return plan_tokens(config, cu_seqlens, grid_thw, n_items, src_row, out_row, win_cu, win_cu_capacity, n_windows);
+  });
+}
+
+// The encoder task.  may_grow: the pinned staging slots may be re-allocated for a batch whose index
+// tables outgrow them (blocks the device); without it such a batch is refused and nothing allocates.
+static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                             int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
+                             void* stream_, bool may_grow, const char* who) {
+  if (!e || !patches || !out_embeddings || !workspace) return fail(CS_ERR_INVALID_ARG, std::string(who) + ": NULL argument");
   if ((reinterpret_cast<uintptr_t>(patches) | reinterpret_cast<uintptr_t>(out_embeddings) |
        reinterpret_cast<uintptr_t>(workspace)) & 15)
-    return fail(CS_ERR_INVALID_ARG, "cs_encode: device pointers must be 16-byte aligned");
+    return fail(CS_ERR_INVALID_ARG, std::string(who) + ": device pointers must be 16-byte aligned");
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const cs_encoder_config& c = e->cfg;
-  BatchPlan p;
-  if (cs_status st = make_plan(e, cu_seqlens, grid_thw, n_items, p)) return st;
+  const BatchPlan* plan_ptr = nullptr;
+  if (cs_status st = get_plan(e, cu_seqlens, grid_thw, n_items, &plan_ptr)) return st;
+  const BatchPlan& p = *plan_ptr;
   const Workspace w = layout_workspace(e, p);
   if (workspace_bytes < w.total)
-    return fail(CS_ERR_WORKSPACE, "cs_encode: workspace has " + std::to_string(workspace_bytes) + " bytes, needs " +
-                                      std::to_string(w.total));
+    return fail(CS_ERR_WORKSPACE, std::string(who) + ": " + (may_grow ? "workspace" : "the static scratch") + " has " +
+                                      std::to_string(workspace_bytes) + " bytes, this batch needs " + std::to_string(w.total));
+  if (!may_grow && p.blob.size() * 4 > std::min(e->stage_cap[0], e->stage_cap[1]))
+    return fail(CS_ERR_WORKSPACE, std::string(who) + ": the index tables of this batch exceed the staging slots");
   unsigned char* ws = static_cast<unsigned char*>(workspace);
 
   // ---- index tables: host -> pinned slot -> workspace, one async copy
@@ -807,6 +911,14 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   return CS_OK;
 }
 
+cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                    int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes, void* stream) {
+  return guarded("cs_encode", [&] {
+    return encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, workspace, workspace_bytes, stream,
+                       true, "cs_encode");
+  });
+}
+
 cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_index, void* dst_seq, int64_t n_rows,
                                 int64_t dst_rows, int32_t hidden, int32_t dtype, int32_t* err_flag, void* stream) {
   if (n_rows < 0 || dst_rows < 0 || hidden <= 0) return fail(CS_ERR_INVALID_ARG, "cs_forward_embeddings: negative size");
@@ -833,8 +945,8 @@ cs_status cs_linear_bf16(const void* A, int64_t lda, const void* W, const float*
   return launch_gemm(c_dtype == CS_BF16 ? EPI_BF16 : EPI_F32, g, static_cast<hipStream_t>(stream));
 }
 
-cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
-                              int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream_) {
+static cs_status attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
+                                  int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream_) {
   if (!qk || !vt || !out || !seg_cu || n_seg <= 0) return fail(CS_ERR_INVALID_ARG, "cs_attention_varlen: NULL argument");
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   std::vector<int32_t> work;
@@ -866,8 +978,13 @@ cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, voi
   return st;
 }
 
-cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_budget, int32_t max_items,
-                        int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid) {
+cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
+                              int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream) {
+  return guarded("cs_attention_varlen", [&] { return attention_varlen(qk, vt, ld_vt, out, seg_cu, n_seg, n_heads, head_dim, stream); });
+}
+
+static cs_status pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_budget, int32_t max_items,
+                            int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid) {
   if (!grid_thw || !selected || !n_selected || n_pending <= 0 || max_items <= 0 || row_budget <= 0)
     return fail(CS_ERR_INVALID_ARG, "cs_pack_batch: NULL argument or non-positive count / budget");
   for (int i = 0; i < n_pending; ++i) {
@@ -892,9 +1009,16 @@ cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_
   return CS_OK;
 }
 
-cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
-                      int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype, int32_t* grid_thw,
-                      int32_t* cu_seqlens, void* stream_) {
+cs_status cs_pack_batch(const int32_t* grid_thw, int32_t n_pending, int64_t row_budget, int32_t max_items,
+                        int32_t* selected, int32_t* n_selected, int32_t* cu_seqlens, int32_t* packed_grid) {
+  return guarded("cs_pack_batch", [&] {
+    return pack_batch(grid_thw, n_pending, row_budget, max_items, selected, n_selected, cu_seqlens, packed_grid);
+  });
+}
+
+static cs_status patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
+                          int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype, int32_t* grid_thw,
+                          int32_t* cu_seqlens, void* stream_) {
   if (!frames || !frame_dims || !patches || n_items <= 0) return fail(CS_ERR_INVALID_ARG, "cs_patchify: NULL argument or no items");
   if ((in_dtype != CS_F32 && in_dtype != CS_BF16) || (out_dtype != CS_F32 && out_dtype != CS_BF16))
     return fail(CS_ERR_INVALID_ARG, "cs_patchify: dtype");
@@ -939,6 +1063,14 @@ cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame
       return st;
   }
   return CS_OK;
+}
+
+cs_status cs_patchify(const void* frames, int32_t in_dtype, const int32_t* frame_dims, int32_t n_items,
+                      int32_t temporal_patch, int32_t patch, void* patches, int32_t out_dtype, int32_t* grid_thw,
+                      int32_t* cu_seqlens, void* stream) {
+  return guarded("cs_patchify", [&] {
+    return patchify(frames, in_dtype, frame_dims, n_items, temporal_patch, patch, patches, out_dtype, grid_thw, cu_seqlens, stream);
+  });
 }
 
 cs_status cs_mfma_ceiling(void* scratch, size_t scratch_bytes, int32_t random_operands, int32_t iters, double* tflops,

@@ -1,7 +1,7 @@
 // cs_channel: the embedding hand-off between an encoder task and an LLM task that run on two
-// streams of one process on one GPU (Sec. 3.1 "Data Forwarding"; Sec. 4.3: the producer's tensor
-// sits in a shared buffer, the consumer is told where, executors wait for tensors that have not
-// arrived).  Slots live in device memory; "arrival" is a HIP event the consumer's stream waits
+// streams of one process on one GPU (Sec. 2.2 "Data Forwarding": the producer's tensor
+// sits in a shared buffer, the consumer is told where; Sec. 2.1 "Request Lifecycle": executors wait
+// for tensors that have not arrived).  Slots live in device memory; "arrival" is a HIP event the consumer's stream waits
 // for, so neither side blocks the host and the rows never leave HBM.
 #include <hip/hip_runtime.h>
 

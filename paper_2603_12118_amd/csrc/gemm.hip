@@ -18,6 +18,8 @@
 // columns in groups of four consecutive n: bias, activations, rotary pairs and 8/16-byte stores
 // all work on registers of one lane.  Inside a K slice the LDS reads of k-step s+1 are issued
 // behind the first MFMAs of k-step s and scheduling barriers pin that order.
+#include <atomic>
+
 #include "common.h"
 
 namespace cs {
@@ -564,10 +566,11 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int LDS = 2 * (BM + BN) * 128;
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, LIGHT_TAIL>;
-  static bool attr_set = false;  // one attribute call per instantiation
-  if (!attr_set) {
+  // one attribute call per instantiation (two threads that both see `false` repeat a harmless call)
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
     CS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   const int tiles_n = (g.N + BN - 1) / BN;
   int tiles = ((g.M + BM - 1) / BM) * tiles_n;

@@ -6,7 +6,7 @@
 * every GEMM shape of the 7B-style vision layer and of the merger at M = 8192 / 2048 rows with a plain
   bf16 store (`cs_linear_bf16`; the fused epilogues are timed in place by `bench.py --breakdown`),
 * `cs_forward_embeddings` at 8, 16 and 32 MB of embedding rows (the tensor sizes for which the paper
-  quotes its forwarding latency, Sec. 4.3),
+  quotes its forwarding latency, Sec. 3 "Sidecar Overhead"),
 * the same sizes through `cs_channel` (producer stream -> slot -> consumer stream): the time from
   the end of the producer's last kernel to the rows being in the consumer's buffer, and the host time
   of the three calls,

@@ -7,7 +7,7 @@ buffer and the placeholder positions.  It holds none of the encoder's
 arithmetic, and both the GPU library's tests and the CPU checker's tests draw
 their inputs from here so that the two sides read identical bytes.
 
-The paper (Sec. 2 "Data Plane", Listing 1) fixes only the split into an
+The paper (Sec. 2.1 "Data Plane", Listing 1) fixes only the split into an
 encoder task that yields one embedding tensor per multimodal item and an LLM
 task that receives those tensors; it evaluates on a request trace that is not
 reproduced here.  The five workloads below stand in for it: synthetic images,

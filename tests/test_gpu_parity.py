@@ -65,7 +65,7 @@ def test_forward_embeddings_c1_positions():
     assert np.array_equal(got[32:96], src) and np.array_equal(got[:32], dst[:32]) and np.array_equal(got[96:], dst[96:])
 
 
-@pytest.mark.parametrize("rows", [1170, 2340, 4681])       # 8, 16, 32 MB of bf16 rows, the sizes of the paper's Sec. 4.3
+@pytest.mark.parametrize("rows", [1170, 2340, 4681])       # 8, 16, 32 MB of bf16 rows, the sizes of the paper's Sec. 3 "Sidecar Overhead"
 def test_forward_embeddings_random_spans_bf16(rows):
     rng = np.random.default_rng(rows)
     dst_rows = 3 * rows + 17

@@ -1,7 +1,7 @@
 """Pins for the CPU checker: every operator of oracle/encoder_oracle.py is compared with
 something other than itself -- a CPU PyTorch library routine, a closed form, an
 invariant, a brute-force loop, or indices worked out by hand.  The paper prints no
-worked numeric example for the encoder task (it fixes only the task boundary, Sec. 3.1
+worked numeric example for the encoder task (it fixes only the task boundary, Sec. 2.2
 and Listing 1), so none of these values comes from the paper.
 """
 import math
