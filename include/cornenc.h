@@ -179,8 +179,23 @@ cs_status cs_encode(cs_encoder* enc, const void* patches, const int32_t* cu_seql
                     int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
                     void* stream);
 
+/* cs_encode for callers that cannot allocate device memory (a tight serving loop, a harness that
+ * forbids hipMalloc, code under stream capture): the same kernels and the same results, bit for bit,
+ * with the workspace taken from a static array of CS_STATIC_SCRATCH_BYTES (64 MiB) that each GPU the
+ * library runs on holds until the process ends.  Calls no hipMalloc / hipFree / hipHostMalloc; the
+ * pinned staging slots keep the size they have.  All arguments as for cs_encode.
+ *  - A batch that needs more workspace than the array holds, or index tables larger than a staging
+ *    slot, is refused with CS_ERR_WORKSPACE before anything is enqueued (cs_encoder_query tells the
+ *    size; the 7B-style vision tower fits about 1300 patches, one 448 x 448 image and more).
+ *  - Every call on a GPU uses that GPU's one array, and the array keeps the last call's contents
+ *    (every buffer in it is written before it is read, so nothing needs clearing): calls that
+ *    overlap in time on one GPU race, whatever their streams and encoders; callers serialise them. */
+#define CS_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+cs_status cs_encode_static(cs_encoder* enc, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                           int32_t n_items, void* out_embeddings, void* stream);
+
 /* Host-only: how often a batch description was found in (hits) or added to (misses) the encoder's
- * plan cache since create, over cs_encoder_query and cs_encode.  Either may be NULL. */
+ * plan cache since create, over cs_encoder_query, cs_encode and cs_encode_static.  Either may be NULL. */
 cs_status cs_encoder_plan_cache_stats(const cs_encoder* enc, int64_t* hits, int64_t* misses);
 
 /* The hand-off on the consumer side (Sec. 2.2 "Data Forwarding": the receiver copies the

@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.cs_encoder_destroy.restype = None
         L.cs_encoder_query.argtypes = [vp, i32p, i32p, C.c_int32, C.POINTER(i64), C.POINTER(C.c_size_t)]
         L.cs_encode.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.cs_encode_static.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp]
         L.cs_encoder_plan_cache_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
         L.cs_forward_embeddings.argtypes = [vp, vp, vp, i64, i64, C.c_int32, C.c_int32, vp, vp]
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
@@ -81,7 +82,7 @@ def lib() -> C.CDLL:
         L.cs_status_string.argtypes = [C.c_int]
         L.cs_status_string.restype = C.c_char_p
         L.cs_last_error.restype = C.c_char_p
-        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encoder_plan_cache_stats",
+        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encode_static", "cs_encoder_plan_cache_stats",
                   "cs_forward_embeddings", "cs_plan_tokens",
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
                   "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
@@ -198,6 +199,20 @@ class Encoder:
                                workspace.data_ptr(), workspace.numel(), _stream(stream)))
         return out, workspace
 
+
+    def cs_encode_static(self, patches, cu_seqlens, grid_thw, out=None, stream=None):
+        """cs_encode with the library's static scratch as workspace (no allocation inside the call when
+        `out` is given).  Returns out."""
+        import torch
+        cu, g = _i32(cu_seqlens), _i32(grid_thw)
+        if out is None:
+            n_out, _ = self.cs_encoder_query(cu, g)
+            dt = torch.bfloat16 if self.cfg.out_dtype == "bf16" else torch.float32
+            out = torch.empty((n_out, self.cfg.out_hidden), dtype=dt, device=patches.device)
+        assert patches.is_contiguous() and out.is_contiguous()
+        _check(lib().cs_encode_static(self._h, patches.data_ptr(), _i32p(cu), _i32p(g), g.shape[0], out.data_ptr(),
+                                      _stream(stream)))
+        return out
 
     def cs_encoder_plan_cache_stats(self):
         hits, misses = C.c_int64(), C.c_int64()

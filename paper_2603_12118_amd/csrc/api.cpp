@@ -115,7 +115,32 @@ struct cs_encoder {
   T* ptr(size_t off) const { return reinterpret_cast<T*>(dev + off); }
 };
 
+// ---- scratch of cs_encode_static: one array per GPU, in the code object's zero-initialised data, held
+// until the process ends.  Host code never uses the array's name as an address (on the host it is
+// only a handle for the lookup below); it uses the per-device address hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[CS_STATIC_SCRATCH_BYTES];
+
 namespace cs {
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Address of the current device's copy of `scratch`, looked up once per device.
+static cs_status static_scratch(void** out) {
+  int dev = -1;
+  CS_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(CS_ERR_UNSUPPORTED, "static scratch: device ordinal out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    CS_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(CS_ERR_HIP, "static scratch: hipGetSymbolAddress returned NULL");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CS_OK;
+}
 
 static cs_status check_config(const cs_encoder_config& c) {
   if (c.struct_size != sizeof(cs_encoder_config)) return fail(CS_ERR_INVALID_ARG, "config.struct_size mismatch");
@@ -596,6 +621,11 @@ static cs_status encoder_create(const cs_encoder_config* config, const cs_tensor
     }
     if (he != hipSuccess) st = fail(CS_ERR_HIP, std::string("cs_encoder_create: ") + hipGetErrorString(he));
     e->dev_bytes = A.host.size();
+    // the address of this device's copy of the static scratch array, for cs_encode_static
+    if (st == CS_OK) {
+      void* unused = nullptr;
+      st = static_scratch(&unused);
+    }
   }
   if (st != CS_OK) {
     cs_encoder_destroy(e);
@@ -916,6 +946,16 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
   return guarded("cs_encode", [&] {
     return encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, workspace, workspace_bytes, stream,
                        true, "cs_encode");
+  });
+}
+
+cs_status cs_encode_static(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                           int32_t n_items, void* out_embeddings, void* stream) {
+  return guarded("cs_encode_static", [&]() -> cs_status {
+    void* ws = nullptr;
+    if (cs_status st = static_scratch(&ws)) return st;
+    return encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, ws, CS_STATIC_SCRATCH_BYTES, stream,
+                       false, "cs_encode_static");
   });
 }
 
