@@ -59,7 +59,8 @@ typedef enum {
   CS_ERR_HIP = 6,         /* a HIP runtime call failed (text in cs_last_error)      */
   CS_ERR_MISSING_WEIGHT = 7,
   CS_ERR_BUSY = 8,        /* cs_channel_acquire: every slot is in use; try again later */
-  CS_ERR_NO_MEMORY = 9    /* a host allocation inside the library failed               */
+  CS_ERR_NO_MEMORY = 9,   /* a host allocation inside the library failed               */
+  CS_ERR_TIMEOUT = 10     /* cs_xchannel_wait: nothing arrived within the time given   */
 } cs_status;
 
 typedef enum { CS_F32 = 0, CS_BF16 = 1 } cs_dtype;
@@ -248,7 +249,7 @@ cs_status cs_forward_embeddings(const void* src, const int64_t* placeholder_inde
  * threads; they are serialised inside.  create allocates the pool (n_slots * slot_bytes rounded up
  * to 256 bytes, one hipMalloc) and two events per slot on the current device; the other calls
  * allocate nothing.  destroy must not be called while work that uses the pool is still running.
- * Two processes would need IPC memory handles for the pool and the events; that is not built. */
+ * Producer and consumer in two processes: cs_xchannel below. */
 typedef struct cs_channel cs_channel;
 typedef enum { CS_SLOT_FREE = 0, CS_SLOT_WRITING = 1, CS_SLOT_READY = 2 } cs_slot_state;
 #define CS_CHANNEL_MAX_SLOTS 1024
@@ -262,6 +263,58 @@ cs_status cs_channel_forward(cs_channel* ch, int32_t slot, const int64_t* placeh
 cs_status cs_channel_release(cs_channel* ch, int32_t slot, void* stream);
 cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, const void** dev_ptr, int64_t* n_rows,
                               int32_t* hidden, int32_t* dtype, int32_t* arrived);
+
+/* cs_xchannel: the same hand-off between TWO PROCESSES on one GPU, as the paper's executors are
+ * (separate processes joined by a per-GPU Sidecar, Sec. 2.1 "Data Plane"; the sender writes the tensor
+ * to a shared buffer, notifies the receiver of its address, the receiver reads it, Sec. 2.2 "Data
+ * Forwarding"; executors wait for tensors that have not arrived, Sec. 2.1 "Request Lifecycle"; the cost
+ * the paper measures for this step: Sec. 3 "Sidecar Overhead").
+ *
+ *   producer process                                     consumer process
+ *   cs_xchannel_create(name, n_slots, slot_bytes)        cs_xchannel_open(name)
+ *   cs_xchannel_acquire  -> slot, dev pointer
+ *   cs_encode(..., out_embeddings = pointer, stream)
+ *   cs_xchannel_publish(slot, rows, ..., stream)  --->   cs_xchannel_wait(timeout) -> slot, rows, width, dtype
+ *                                                        cs_xchannel_forward(slot, index, dst, stream)
+ *
+ * The pool of slots is device memory of the producer that the consumer maps through an IPC memory
+ * handle (the pool stays under 2 GiB; rows never leave HBM).  The slot table and the notification queue
+ * live in a POSIX shared-memory segment "/cornenc-<name>".  publish enqueues a host function on
+ * `producer_stream` behind everything enqueued so far (which must include all work that writes the
+ * slot); when that work has finished, the function marks the slot READY and queues its number: a slot
+ * the consumer hears of is complete in memory.  forward enqueues the row scatter of
+ * cs_forward_embeddings reading the slot (same argument rules, same err_flag behaviour) and behind it a
+ * host function that hands the slot back (FREE).  No call blocks except cs_xchannel_wait, which polls
+ * the queue for at most timeout_us microseconds (CS_ERR_TIMEOUT then; 0 = look once).
+ *
+ * Slot states: FREE -> WRITING (acquire) -> PUBLISHING (publish called) -> READY (producer's work done,
+ * number queued) -> DRAINING (forward called) -> FREE (placement done).  release returns a WRITING slot
+ * to FREE (a cancelled request).  A call on a slot in another state than it needs is
+ * CS_ERR_INVALID_ARG and changes nothing; acquire returns CS_ERR_BUSY when no slot is FREE and
+ * CS_ERR_WORKSPACE when bytes == 0 or bytes > slot_bytes; publish CS_ERR_SHAPE for more rows than were
+ * reserved.  describe reports a slot (any out pointer may be NULL); t_ready_ns / t_placed_ns are
+ * CLOCK_MONOTONIC readings taken when the slot last became READY / was last placed (one clock for both
+ * processes, so their difference is the time the hand-off added after the producer's last kernel).
+ * One producer process (any number of its threads and streams) and one consumer thread per channel.
+ * create allocates (one hipMalloc, one shared segment) and open maps; the other calls allocate nothing.
+ * The creator closes last: cs_xchannel_close of the creator frees the pool and removes the segment. */
+typedef struct cs_xchannel cs_xchannel;
+typedef enum { CS_XSLOT_FREE = 0, CS_XSLOT_WRITING = 1, CS_XSLOT_PUBLISHING = 2, CS_XSLOT_READY = 3,
+               CS_XSLOT_DRAINING = 4 } cs_xslot_state;
+#define CS_XCHANNEL_MAX_SLOTS 256
+cs_status cs_xchannel_create(const char* name, int32_t n_slots, size_t slot_bytes, cs_xchannel** out);
+cs_status cs_xchannel_open(const char* name, cs_xchannel** out);
+void cs_xchannel_close(cs_xchannel* ch);
+cs_status cs_xchannel_acquire(cs_xchannel* ch, size_t bytes, int32_t* slot, void** dev_ptr);
+cs_status cs_xchannel_publish(cs_xchannel* ch, int32_t slot, int64_t n_rows, int32_t hidden, int32_t dtype,
+                              void* producer_stream);
+cs_status cs_xchannel_wait(cs_xchannel* ch, int64_t timeout_us, int32_t* slot, int64_t* n_rows, int32_t* hidden,
+                           int32_t* dtype);
+cs_status cs_xchannel_forward(cs_xchannel* ch, int32_t slot, const int64_t* placeholder_index, void* dst_seq,
+                              int64_t dst_rows, int32_t* err_flag, void* consumer_stream);
+cs_status cs_xchannel_release(cs_xchannel* ch, int32_t slot);
+cs_status cs_xchannel_describe(cs_xchannel* ch, int32_t slot, int32_t* state, const void** dev_ptr, int64_t* n_rows,
+                               int32_t* hidden, int32_t* dtype, int64_t* t_ready_ns, int64_t* t_placed_ns);
 
 /* Host-only (no GPU needed) view of the token plan cs_encode builds for a vit batch with this
  * configuration; also validates the batch description exactly as cs_encode does.

@@ -19,7 +19,8 @@ CS_F32, CS_BF16 = 0, 1
 CS_ARCH_VIT, CS_ARCH_AUDIO, CS_ARCH_VIT_CLS = 0, 1, 2
 CS_ORDER_RASTER, CS_ORDER_MERGE_MAJOR = 0, 1
 CS_SLOT_FREE, CS_SLOT_WRITING, CS_SLOT_READY = 0, 1, 2
-CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY, CS_ERR_NO_MEMORY = 1, 2, 3, 5, 8, 9
+CS_ERR_INVALID_ARG, CS_ERR_SHAPE, CS_ERR_WORKSPACE, CS_ERR_UNSUPPORTED, CS_ERR_BUSY, CS_ERR_NO_MEMORY, CS_ERR_TIMEOUT = 1, 2, 3, 5, 8, 9, 10
+CS_XSLOT_FREE, CS_XSLOT_WRITING, CS_XSLOT_PUBLISHING, CS_XSLOT_READY, CS_XSLOT_DRAINING = 0, 1, 2, 3, 4
 STEPS = {"front": 1, "norm": 2, "qkv": 3, "attn_window": 4, "attn_full": 5, "proj": 6, "mlp_up": 7, "mlp_down": 8,
          "back": 9}
 
@@ -75,6 +76,17 @@ def lib() -> C.CDLL:
         L.cs_channel_forward.argtypes = [vp, C.c_int32, vp, vp, i64, vp, vp]
         L.cs_channel_release.argtypes = [vp, C.c_int32, vp]
         L.cs_channel_describe.argtypes = [vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(i64), i32p, i32p, i32p]
+        L.cs_xchannel_create.argtypes = [C.c_char_p, C.c_int32, C.c_size_t, C.POINTER(vp)]
+        L.cs_xchannel_open.argtypes = [C.c_char_p, C.POINTER(vp)]
+        L.cs_xchannel_close.argtypes = [vp]
+        L.cs_xchannel_close.restype = None
+        L.cs_xchannel_acquire.argtypes = [vp, C.c_size_t, i32p, C.POINTER(vp)]
+        L.cs_xchannel_publish.argtypes = [vp, C.c_int32, i64, C.c_int32, C.c_int32, vp]
+        L.cs_xchannel_wait.argtypes = [vp, i64, i32p, C.POINTER(i64), i32p, i32p]
+        L.cs_xchannel_forward.argtypes = [vp, C.c_int32, vp, vp, i64, vp, vp]
+        L.cs_xchannel_release.argtypes = [vp, C.c_int32]
+        L.cs_xchannel_describe.argtypes = [vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(i64), i32p, i32p,
+                                           C.POINTER(i64), C.POINTER(i64)]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
         L.cs_encoder_time_every.argtypes = [vp, C.c_int32]
@@ -87,7 +99,9 @@ def lib() -> C.CDLL:
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
                   "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
                   "cs_channel_acquire", "cs_channel_publish", "cs_channel_forward", "cs_channel_release",
-                  "cs_channel_describe"):
+                  "cs_channel_describe", "cs_xchannel_create", "cs_xchannel_open", "cs_xchannel_acquire",
+                  "cs_xchannel_publish", "cs_xchannel_wait", "cs_xchannel_forward", "cs_xchannel_release",
+                  "cs_xchannel_describe"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -319,6 +333,61 @@ class Channel:
                                          C.byref(dtype), C.byref(arrived)))
         return {"state": state.value, "ptr": ptr.value, "n_rows": rows.value, "hidden": hidden.value,
                 "dtype": dtype.value, "arrived": arrived.value}
+
+
+class XChannel:
+    """Owns a cs_xchannel handle (the hand-off between two processes): `create=True` in the producer
+    process, `create=False` (open by name) in the consumer process."""
+
+    def __init__(self, name: str, n_slots: int = 0, slot_bytes: int = 0, create: bool = True):
+        self._h = C.c_void_p()
+        if create:
+            _check(lib().cs_xchannel_create(name.encode(), n_slots, slot_bytes, C.byref(self._h)))
+        else:
+            _check(lib().cs_xchannel_open(name.encode(), C.byref(self._h)))
+
+    def close(self) -> None:
+        if self._h:
+            lib().cs_xchannel_close(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    slot_tensor = Channel.slot_tensor
+
+    def cs_xchannel_acquire(self, nbytes: int):
+        """-> (status, slot, device address)"""
+        slot, ptr = C.c_int32(-1), C.c_void_p()
+        st = lib().cs_xchannel_acquire(self._h, nbytes, C.byref(slot), C.byref(ptr))
+        return st, slot.value, ptr.value
+
+    def cs_xchannel_publish(self, slot: int, n_rows: int, hidden: int, dtype: int, producer_stream=None) -> int:
+        return lib().cs_xchannel_publish(self._h, slot, n_rows, hidden, dtype, _stream(producer_stream))
+
+    def cs_xchannel_wait(self, timeout_us: int):
+        """-> (status, slot, n_rows, hidden, dtype)"""
+        slot, rows, hidden, dtype = C.c_int32(-1), C.c_int64(), C.c_int32(), C.c_int32()
+        st = lib().cs_xchannel_wait(self._h, timeout_us, C.byref(slot), C.byref(rows), C.byref(hidden), C.byref(dtype))
+        return st, slot.value, rows.value, hidden.value, dtype.value
+
+    def cs_xchannel_forward(self, slot: int, placeholder_index, dst_seq, err_flag=None, consumer_stream=None) -> int:
+        return lib().cs_xchannel_forward(self._h, slot, placeholder_index.data_ptr(), dst_seq.data_ptr(), dst_seq.shape[0],
+                                         err_flag.data_ptr() if err_flag is not None else None, _stream(consumer_stream))
+
+    def cs_xchannel_release(self, slot: int) -> int:
+        return lib().cs_xchannel_release(self._h, slot)
+
+    def cs_xchannel_describe(self, slot: int):
+        state, ptr, rows = C.c_int32(), C.c_void_p(), C.c_int64()
+        hidden, dtype, t_ready, t_placed = C.c_int32(), C.c_int32(), C.c_int64(), C.c_int64()
+        _check(lib().cs_xchannel_describe(self._h, slot, C.byref(state), C.byref(ptr), C.byref(rows), C.byref(hidden),
+                                          C.byref(dtype), C.byref(t_ready), C.byref(t_placed)))
+        return {"state": state.value, "ptr": ptr.value, "n_rows": rows.value, "hidden": hidden.value,
+                "dtype": dtype.value, "t_ready_ns": t_ready.value, "t_placed_ns": t_placed.value}
 
 
 def cs_forward_embeddings_raw(src_ptr, idx_ptr, dst_ptr, n_rows, dst_rows, hidden, dtype, err_ptr=None, stream=0) -> int:

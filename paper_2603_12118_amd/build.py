@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcornenc.so")
-SOURCES = ["api.cpp", "plan.cpp", "channel.cpp", "gemm.hip", "attention.hip", "elementwise.hip", "probe.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "channel.cpp", "xchannel.cpp", "gemm.hip", "attention.hip", "elementwise.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -576,6 +576,7 @@ const char* cs_status_string(cs_status s) {
     case CS_ERR_MISSING_WEIGHT: return "missing weight";
     case CS_ERR_BUSY: return "busy";
     case CS_ERR_NO_MEMORY: return "out of host memory";
+    case CS_ERR_TIMEOUT: return "timed out";
   }
   return "unknown status";
 }

@@ -10,6 +10,10 @@
 * the same sizes through `cs_channel` (producer stream -> slot -> consumer stream): the time from
   the end of the producer's last kernel to the rows being in the consumer's buffer, and the host time
   of the three calls,
+* the same sizes through `cs_xchannel` (producer PROCESS -> slot in HBM -> consumer PROCESS on the same
+  GPU, two child processes started here): the time from the producer's stream having finished its
+  work on the slot (its host function) to the placement having finished in the consumer (its host
+  function), on the clock both processes share,
 * `cs_patchify` on the eight 448x448 images of the benchmark batch.
 
 Attention on its own at segment sizes 64 / 1024 / 8192 is what `bench.py --breakdown` reports as the
@@ -74,6 +78,70 @@ def _channel(B, src, idx, dst, n=20, warm=3):
     return {"us_producer_done_to_placed": sum(pairs) / n, "host_us": host / n * 1e6}
 
 
+def _xchannel(sizes_mb, hidden, n=20):
+    """Two child processes (paper_2603_12118_amd.channel_peer) on this GPU, one tensor at a time."""
+    import json as J
+    import os
+    import subprocess
+    import sys
+    import uuid
+    import numpy as np
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    name = "mb" + uuid.uuid4().hex[:10]
+
+    def start(role):
+        p = subprocess.Popen([sys.executable, "-u", "-m", "paper_2603_12118_amd.channel_peer", role, name], cwd=root,
+                             stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True)
+        return p
+
+    def call(p, op=None, **kw):
+        if op is not None:
+            p.stdin.write(J.dumps({"op": op, **kw}) + "\n")
+            p.stdin.flush()
+        while True:
+            line = p.stdout.readline()
+            if not line:
+                raise RuntimeError("channel peer ended")
+            if line.strip().startswith("{"):
+                return J.loads(line)
+
+    prod, cons = start("producer"), start("consumer")
+    out = []
+    try:
+        call(prod), call(cons)
+        max_rows = max(sizes_mb) * (1 << 20) // (hidden * 2)
+        call(prod, "create", n_slots=2, slot_bytes=max_rows * hidden * 2)
+        call(cons, "open")
+        call(cons, "buffers", count=1, rows=4 * max_rows, hidden=hidden, seed=1)
+        rng = np.random.default_rng(0)
+        for mb in sizes_mb:
+            rows = mb * (1 << 20) // (hidden * 2)
+            idx = rng.permutation(4 * max_rows)[:rows].tolist()
+            lat = []
+            for i in range(n + 3):
+                a = call(prod, "acquire", nbytes=rows * hidden * 2)
+                assert a["st"] == 0, a
+                assert call(prod, "fill", slot=a["slot"], ptr=a["ptr"], n=rows, hidden=hidden)["st"] == 0
+                w = call(cons, "wait", timeout_us=10_000_000)
+                assert w["st"] == 0 and w["slot"] == a["slot"], w
+                assert call(cons, "forward", slot=w["slot"], dst=0, index=idx)["st"] == 0
+                assert call(cons, "settle", slot=w["slot"], timeout_us=10_000_000)["state"] == 0
+                d = call(cons, "describe", slot=w["slot"])
+                if i >= 3:
+                    lat.append((d["t_placed_ns"] - d["t_ready_ns"]) / 1e3)
+            lat.sort()
+            out.append({"MB": mb, "rows": rows, "us_median": lat[len(lat) // 2], "us_min": lat[0], "us_max": lat[-1]})
+    finally:
+        for p in (cons, prod):
+            try:
+                p.stdin.write(J.dumps({"op": "quit"}) + "\n")
+                p.stdin.flush()
+                p.wait(timeout=60)
+            except Exception:
+                p.kill()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--json", action="store_true")
@@ -102,6 +170,7 @@ def main() -> int:
         res["forward_embeddings"].append({"MB": mb, "rows": rows, "us": s * 1e6, "GBs": nbytes / s / 1e9})
         res["channel"].append({"MB": mb, "rows": rows, **_channel(B, src, idx, dst)})
         del src, dst, idx
+    res["xchannel"] = _xchannel((8, 16, 32), hidden)
     px = torch.rand(8 * 3 * 448 * 448, device=dev, generator=g)
     dims = [(1, 448, 448)] * 8
     s = _time(lambda: B.cs_patchify(px, dims, temporal_patch=2))
@@ -121,6 +190,9 @@ def main() -> int:
     print("| cs_channel (publish -> placed) | rows | us after the producer's last kernel | host us for the 3 calls |\n|---|---|---|---|")
     for r in res["channel"]:
         print(f"| {r['MB']} MB | {r['rows']} | {r['us_producer_done_to_placed']:.1f} | {r['host_us']:.1f} |")
+    print("| cs_xchannel (two processes; producer's work done -> placed in the consumer) | rows | us median | min | max |\n|---|---|---|---|---|")
+    for r in res["xchannel"]:
+        print(f"| {r['MB']} MB | {r['rows']} | {r['us_median']:.1f} | {r['us_min']:.1f} | {r['us_max']:.1f} |")
     r = res["patchify"]
     print(f"cs_patchify, {r['workload']}: {r['us']:.1f} us, {r['GBs']:.0f} GB/s")
     return 0
