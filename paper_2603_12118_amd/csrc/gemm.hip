@@ -18,6 +18,8 @@
 // columns in groups of four consecutive n: bias, activations, rotary pairs and 8/16-byte stores
 // all work on registers of one lane.  Inside a K slice the LDS reads of k-step s+1 are issued
 // behind the first MFMAs of k-step s and scheduling barriers pin that order.
+#include <stdlib.h>
+
 #include <atomic>
 
 #include "common.h"
@@ -512,7 +514,32 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool LIGHT_TAIL>
+// What a launch does with the tiles that would leave the chip mostly idle:
+//  TAIL_LIGHT (M not a multiple of BM): the workgroups behind those of the full tile rows take the
+//    remaining rows in 64-row tiles (same threads, every wave a 64 x BN/waves strip): they stream the
+//    same W slices but do a quarter of the MFMAs, so that tile row costs microseconds instead of a round
+//    of the chip.
+//  TAIL_SPLIT (M a multiple of BM, the last round of the chip at most half full): the tiles of that
+//    last round are cut in two along M and run as BM/2-row tiles by twice as many workgroups, so the
+//    round takes little more than half as long.  A round costs the same however few of its tiles are
+//    there (measured: 864 tiles of 256 x 256 take as long as 1024), and 8192 x 6912 is 3 3/8 rounds.
+enum { TAIL_NONE = 0, TAIL_LIGHT = 1, TAIL_SPLIT = 2 };
+constexpr int CHIP_CUS = 256;
+
+// tile id -> first row / column.  Ids walk the tile grid in bands of GROUP_M tile rows, row index
+// fastest, so the ~32 tiles an XCD runs at a time form a GROUP_M x 8 block that shares GROUP_M slices
+// of A and 8 slices of W per k-step (an L2 miss on every W byte otherwise: measured 427 clocks average
+// L2 read latency and the L1 miss queue full 58 % of the time).
+template <int BM, int BN>
+__device__ __forceinline__ void tile_origin(int id, int tiles_m, int tiles_n, int& m0, int& n0) {
+  constexpr int GROUP_M = 4;
+  const int band = id / (GROUP_M * tiles_n), in_band = id - band * (GROUP_M * tiles_n);
+  const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
+  m0 = (band * GROUP_M + in_band % band_rows) * BM;
+  n0 = (in_band / band_rows) * BN;
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
   if (gridDim.y > 1) {   // split K (plain fp32 partial sums only): this workgroup's part of A, W and of the output
@@ -524,13 +551,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int tiles_n = (N + BN - 1) / BN;
   int tiles_m = (M + BM - 1) / BM;
   int nb = gridDim.x;
-  // LIGHT_TAIL (a separate instantiation, chosen at launch when M is not a multiple of BM and the last,
-  // partly empty tile row is a noticeable share of the launch): the workgroups behind those of the
-  // full tile rows take the remaining rows in 64-row tiles (same threads, every wave a 64 x BN/waves
-  // strip): they stream the same W slices but do a quarter of the MFMAs, so that tile row costs
-  // microseconds instead of a round of the chip.
-  constexpr bool LIGHT = LIGHT_TAIL;
-  static_assert(!LIGHT_TAIL || light_tail<BN, WGM, WGN, EPI>(), "no 64-row tile for this shape");
+  constexpr bool LIGHT = TAIL == TAIL_LIGHT;
+  static_assert(!LIGHT || light_tail<BN, WGM, WGN, EPI>(), "no 64-row tile for this shape");
+  static_assert(TAIL != TAIL_SPLIT || (BM / 2 / WGM) % 32 == 0, "half tiles need whole 32-row blocks per wave");
+  if constexpr (TAIL == TAIL_SPLIT) {
+    // workgroups [0, n_main) run the full rounds; the rest each take half of a tile of the last round
+    const int n_main = (tiles_m * tiles_n / CHIP_CUS) * CHIP_CUS;
+    if ((int)blockIdx.x >= n_main) {
+      const int t = blockIdx.x - n_main;
+      int m0, n0;
+      tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
+      tile_body<BM / 2, BN, WGM, WGN, EPI>(g, smem, m0 + (t & 1) * (BM / 2), n0);
+      return;
+    }
+    nb = n_main;
+  }
   if constexpr (LIGHT) {
     const int full_m = M / BM, n_main = full_m * tiles_n;
     if ((int)blockIdx.x >= n_main) {
@@ -544,28 +579,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   }
 
   // workgroup -> tile.  Consecutive workgroups land on different XCDs (b % 8), each with its own
-  // L2, so every XCD gets a contiguous range of tile ids; ids walk the tile grid in bands of GROUP_M
-  // tile rows, row index fastest, so the ~32 tiles an XCD runs at a time form a GROUP_M x 8 block
-  // that shares GROUP_M slices of A and 8 slices of W per k-step (an L2 miss on every W byte
-  // otherwise: measured 427 clocks average L2 read latency and the L1 miss queue full 58 % of the time).
-  constexpr int GROUP_M = 4;
+  // L2, so every XCD gets a contiguous range of tile ids.
   int bid = blockIdx.x;
   {
     const int xcd = bid & 7, idx = bid >> 3;
     const int per = nb >> 3, rem = nb & 7;
     bid = xcd * per + (xcd < rem ? xcd : rem) + idx;
   }
-  const int band = bid / (GROUP_M * tiles_n), in_band = bid - band * (GROUP_M * tiles_n);
-  const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
-  const int m0 = (band * GROUP_M + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
+  int m0, n0;
+  tile_origin<BM, BN>(bid, tiles_m, tiles_n, m0, n0);
   tile_body<BM, BN, WGM, WGN, EPI>(g, smem, m0, n0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool LIGHT_TAIL>
+// Measurement switch: CS_GEMM_NO_TAIL_SPLIT=1 in the environment keeps whole tiles in the last round, so
+// the effect of the half tiles can be measured from the committed tree (read once).
+static bool tail_split_off() {
+  static const bool off = [] {
+    const char* v = getenv("CS_GEMM_NO_TAIL_SPLIT");
+    return v && *v && *v != '0';
+  }();
+  return off;
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int LDS = 2 * (BM + BN) * 128;
-  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, LIGHT_TAIL>;
+  auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   // one attribute call per instantiation (two threads that both see `false` repeat a harmless call)
   static std::atomic<bool> attr_set{false};
   if (!attr_set.load(std::memory_order_acquire)) {
@@ -574,8 +614,10 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   }
   const int tiles_n = (g.N + BN - 1) / BN;
   int tiles = ((g.M + BM - 1) / BM) * tiles_n;
-  if (LIGHT_TAIL)   // full tile rows, then the remaining rows in 64-row tiles
+  if (TAIL == TAIL_LIGHT)   // full tile rows, then the remaining rows in 64-row tiles
     tiles = (g.M / BM) * tiles_n + ((g.M % BM + 63) / 64) * tiles_n;
+  if (TAIL == TAIL_SPLIT)   // the tiles of the last round twice, as half tiles
+    tiles += tiles % CHIP_CUS;
   hipLaunchKernelGGL(kern, dim3(tiles, g.splits > 1 ? g.splits : 1), dim3(NT), LDS, stream, g);
   CS_HIP(hipGetLastError());
   return CS_OK;
@@ -585,9 +627,15 @@ template <int BM, int BN, int WGM, int WGN, int EPI>
 static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
   // the light-tail variant where the last, partly empty tile row is at least 1/64 of the tile rows
   if constexpr (light_tail<BN, WGM, WGN, EPI>()) {
-    if (g.M % BM != 0 && (g.M + BM - 1) / BM <= 64) return launch_one<BM, BN, WGM, WGN, EPI, true>(g, stream);
+    if (g.M % BM != 0 && (g.M + BM - 1) / BM <= 64) return launch_one<BM, BN, WGM, WGN, EPI, TAIL_LIGHT>(g, stream);
   }
-  return launch_one<BM, BN, WGM, WGN, EPI, false>(g, stream);
+  // half tiles for a last round that is at most half full (the big tile only: that is where a round is long)
+  if constexpr (BM == 256 && BN == 256) {
+    const int tiles = (g.M / BM) * ((g.N + BN - 1) / BN), tail = tiles % CHIP_CUS;
+    if (g.M % BM == 0 && g.splits <= 1 && tiles > CHIP_CUS && tail > 0 && tail <= CHIP_CUS / 2 && !tail_split_off())
+      return launch_one<BM, BN, WGM, WGN, EPI, TAIL_SPLIT>(g, stream);
+  }
+  return launch_one<BM, BN, WGM, WGN, EPI, TAIL_NONE>(g, stream);
 }
 
 template <int EPI>
