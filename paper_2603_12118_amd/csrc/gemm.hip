@@ -34,6 +34,28 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void lds_void;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// The MFMA shape (build-time switch for measurement: -DCS_GEMM_MFMA16=0 gives v_mfma_f32_32x32x16_bf16).
+// Both do 1024 FLOP per SIMD and clock; on random operands at the board's power limit a bare loop of
+// 16x16x32 sustains about 12 % more (see cs_mfma_ceiling and the measurement notes).
+#ifndef CS_GEMM_MFMA16
+#define CS_GEMM_MFMA16 1
+#endif
+// The 16x16x32 shape is used by the eight-wave tiles (two waves per SIMD).  With one wave per SIMD (the
+// four-wave tiles) it is slower: every other instruction of the wave delays an MFMA of 16 clocks more
+// than one of 32 (measured: down projection 67 -> 106 us).
+template <int NWAVES>
+constexpr bool use_mfma16() { return CS_GEMM_MFMA16 != 0 && NWAVES >= 8; }
+
+// A wave's accumulators are kept per 32 x 32 block of C^T (or C), 16 registers per lane = 4 groups q of
+// 4 consecutive columns of one row.  Which row and columns a lane's group q holds depends on the MFMA:
+//   32x32x16: one block per MFMA;      row lane % 32,                columns 8q + 4 (lane / 32) ...
+//   16x16x32: four MFMAs per block;    row 16 (q / 2) + lane % 16,   columns 16 (q % 2) + 4 (lane / 16) ...
+// ("row" is the second operand's index, "column" the first operand's.)
+template <bool MFMA16>
+__device__ __forceinline__ int blk_row(int q, int lane) { return MFMA16 ? 16 * (q >> 1) + (lane & 15) : (lane & 31); }
+template <bool MFMA16>
+__device__ __forceinline__ int blk_col(int q, int lane) { return MFMA16 ? 16 * (q & 1) + 4 * (lane >> 4) : 8 * q + 4 * (lane >> 5); }
 // four floats -> four bf16 (v_cvt_pk_bf16_f32, round to nearest even), as 8 bytes
 __device__ __forceinline__ u32x2 pack4(float a, float b, float c, float d) {
   const f32x4 v = {a, b, c, d};
@@ -55,23 +77,23 @@ __device__ __forceinline__ float silu_f(float z) {
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
-// v[b][q] holds columns b*32 + 8q + 4*(lane/32) .. +3 of row lane%32 of a 32 x (NB*32) block.
+// v[b][q] holds columns b*32 + blk_col(q) .. +3 of row blk_row(q) of a 32 x (NB*32) block.
 // The block's element (r, c) goes to out[rowmap(row0 + r) * ld + col0 + c] for row0 + r < row_end,
 // col0 + c < col_end (col_end - col0 a multiple of 4); ACCUM adds to what is there (fp32 only).
-template <int NB, typename T, bool ACCUM>
+template <int NB, typename T, bool ACCUM, bool MFMA16>
 __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&v)[NB][4], T* out, int64_t ld,
                                             const int32_t* row_map, int row0, int row_end, int col0, int col_end,
                                             bool wide, bool wt, const f32x4* held = nullptr) {
   constexpr int ES = (int)sizeof(T);
   static_assert(NB * 32 * ES <= 128, "a chunk row holds 128 bytes");
   static_assert(!ACCUM || ES == 4, "accumulation is for fp32 outputs");
-  const int lane = threadIdx.x & 63, l31 = lane & 31, lhi = lane >> 5;
+  const int lane = threadIdx.x & 63;
   asm volatile("" ::: "memory");
 #pragma unroll
   for (int b = 0; b < NB; ++b)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      unsigned char* p = chunk + l31 * CHUNK_STRIDE + (b * 32 + 8 * q + 4 * lhi) * ES;
+      unsigned char* p = chunk + blk_row<MFMA16>(q, lane) * CHUNK_STRIDE + (b * 32 + blk_col<MFMA16>(q, lane)) * ES;
       if constexpr (ES == 2) *reinterpret_cast<u32x2*>(p) = pack4(v[b][q][0], v[b][q][1], v[b][q][2], v[b][q][3]);
       else *reinterpret_cast<f32x4*>(p) = v[b][q];
     }
@@ -93,7 +115,7 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
     T* dst = out + row * ld + n;
     if constexpr (ES == 4) {
       f32x4* d4 = reinterpret_cast<f32x4*>(dst);
-      if constexpr (ACCUM) *d4 = (held ? held[it] : *d4) + piece;
+      if constexpr (ACCUM) store16(d4, (held ? held[it] : *d4) + piece, wt);
       else store16(d4, piece, wt);
     } else {
       if (wide && n + 8 <= col_end) {
@@ -108,6 +130,18 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
   asm volatile("" ::: "memory");
 }
 
+// Cache-policy bits of the operand loads (build-time switches for measurement: -DCS_GEMM_W_AUX=2 marks the
+// W loads non-temporal, 1 = sc0, 16 = sc1; likewise CS_GEMM_A_AUX for the A loads).
+#ifndef CS_GEMM_W_AUX
+#define CS_GEMM_W_AUX 0
+#endif
+#ifndef CS_GEMM_RESADD_WT     // 1: the residual-add epilogue stores write-through like the others
+#define CS_GEMM_RESADD_WT 1
+#endif
+#ifndef CS_GEMM_A_AUX
+#define CS_GEMM_A_AUX 0
+#endif
+
 // Issues the LDS-direct loads of one 64-wide K slice: every wave instruction moves 64 x 16 bytes
 // from the lanes' global addresses to 1 KB of LDS starting at a wave-uniform address, in lane order.
 template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
@@ -115,10 +149,10 @@ __device__ __forceinline__ void issue_slice(const bf16_t* const* ap, const bf16_
                                             unsigned char* stage, int wave) {
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i)
-    __builtin_amdgcn_global_load_lds(ap[i] + kt * 64, (lds_void*)(uintptr_t)(stage + (i * NWAVES + wave) * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(ap[i] + kt * 64, (lds_void*)(uintptr_t)(stage + (i * NWAVES + wave) * 1024), 16, 0, CS_GEMM_A_AUX);
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i)
-    __builtin_amdgcn_global_load_lds(bp[i] + kt * 64, (lds_void*)(uintptr_t)(stage + BM * 128 + (i * NWAVES + wave) * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(bp[i] + kt * 64, (lds_void*)(uintptr_t)(stage + BM * 128 + (i * NWAVES + wave) * 1024), 16, 0, CS_GEMM_W_AUX);
 }
 
 // One of the A_LOADS + B_LOADS loads of a slice, by index.
@@ -126,10 +160,10 @@ template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
 __device__ __forceinline__ void issue_one(const bf16_t* const* ap, const bf16_t* const* bp, int l, int kt,
                                           unsigned char* stage, int wave) {
   if (l < A_LOADS)
-    __builtin_amdgcn_global_load_lds(ap[l] + kt * 64, (lds_void*)(uintptr_t)(stage + (l * NWAVES + wave) * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(ap[l] + kt * 64, (lds_void*)(uintptr_t)(stage + (l * NWAVES + wave) * 1024), 16, 0, CS_GEMM_A_AUX);
   else
     __builtin_amdgcn_global_load_lds(bp[l - A_LOADS] + kt * 64,
-                                     (lds_void*)(uintptr_t)(stage + BM * 128 + ((l - A_LOADS) * NWAVES + wave) * 1024), 16, 0, 0);
+                                     (lds_void*)(uintptr_t)(stage + BM * 128 + ((l - A_LOADS) * NWAVES + wave) * 1024), 16, 0, CS_GEMM_W_AUX);
 }
 
 // One 64-wide K slice of a wave's MFMAs.  PREFETCH: the loads of slice kn go out one at a time
@@ -143,9 +177,61 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
                                         int lhi, int wave, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
   constexpr int NWAVES = WGM * WGN;
+  constexpr bool MFMA16 = use_mfma16<NWAVES>();
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
   constexpr int RD_PER = 2;     // LDS reads of the next k-step issued behind each of the first MFMAs
   constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
+  if constexpr (MFMA16) {
+    // Two k-steps of 32 with v_mfma_f32_16x16x32_bf16; a_rd / b_rd address row lane % 16 of the wave's first
+    // 16-row fragment and sw = (lane % 16) / 2; lhi = lane / 16 is the lane's 16-byte piece of a k-step's 64
+    // bytes.  Fragment i of A pairs with fragment j of W into quarter 2 (i % 2) + j % 2 of block (i / 2, j / 2).
+    // The operand with fewer fragments per wave is held, double-buffered over the two k-steps (the second
+    // k-step's come in behind the first MFMAs); the other is streamed through a ring of four registers
+    // sets, each fragment requested three rows of MFMAs before its turn, so 48 registers hold the operands
+    // whatever the wave tile (a full double buffer of a 128 x 64 tile would take 96).
+    constexpr int TM16 = 2 * TM, TN16 = 2 * TN;
+    constexpr bool STREAM_A = TM16 >= TN16;
+    constexpr int NO = STREAM_A ? TM16 : TN16;      // streamed fragments per k-step
+    constexpr int NI = STREAM_A ? TN16 : TM16;      // held fragments per k-step
+    const int s_rd = STREAM_A ? a_rd : b_rd, h_rd = STREAM_A ? b_rd : a_rd;
+    const int coff0 = (lhi ^ sw) << 4, coff1 = ((4 + lhi) ^ sw) << 4;
+    bf16x8 hf[2][NI], sf[4];
+    auto read_streamed = [&](int r) {   // row r of the 2 * NO rows of this slice
+      return *reinterpret_cast<const bf16x8*>(cur + s_rd + (r % NO) * 16 * 128 + (r < NO ? coff0 : coff1));
+    };
+#pragma unroll
+    for (int j = 0; j < NI; ++j) hf[0][j] = *reinterpret_cast<const bf16x8*>(cur + h_rd + j * 16 * 128 + coff0);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) sf[r] = read_streamed(r);
+#pragma unroll
+    for (int r = 0; r < 2 * NO; ++r) {
+      const int ks = r / NO, o = r % NO;
+#pragma unroll
+      for (int in = 0; in < NI; ++in) {
+        const int n = o * NI + in;
+        const int i = STREAM_A ? o : in, j = STREAM_A ? in : o;
+        const int quarter = 2 * (i & 1) + (j & 1);
+        const bf16x8 fa = STREAM_A ? sf[r & 3] : hf[ks][in], fw = STREAM_A ? hf[ks][in] : sf[r & 3];
+        f32x4 c;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = acc[i >> 1][j >> 1][4 * quarter + e];
+        if (W_FIRST) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw, fa, c, 0, 0, 0);
+        else c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fw, c, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i >> 1][j >> 1][4 * quarter + e] = c[e];
+        if (PREFETCH && ks == 0) {
+          constexpr int LT = A_LOADS + B_LOADS, SLOTS = NO * NI;
+#pragma unroll
+          for (int l = 0; l < LT; ++l)
+            if (l * SLOTS / LT == n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
+        }
+        if (in == 0 && r + 3 < 2 * NO) sf[(r + 3) & 3] = read_streamed(r + 3);
+        if (ks == 0 && n < NI) hf[1][n] = *reinterpret_cast<const bf16x8*>(cur + h_rd + n * 16 * 128 + coff1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    return;
+  }
   bf16x8 af[2][TM], bfr[2][TN];
   {
     const int coff = (lhi ^ sw) << 4;
@@ -197,15 +283,18 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
+  constexpr bool MFMA16 = use_mfma16<NWAVES>();
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N, K = g.K;
-  const int l31 = lane & 31, lhi = lane >> 5;
-  const int a_rd = (wm * WM + l31) * 128;
-  const int b_rd = BM * 128 + (wn * WN + l31) * 128;
-  const int sw = (l31 >> 1) & 7;
+  // the lane's row inside an operand fragment (32 rows, or 16 for the 16x16x32 shape) and its 16-byte
+  // piece of a k-step; sw = the row's share of the LDS chunk swizzle
+  const int lrow = MFMA16 ? (lane & 15) : (lane & 31), lhi = MFMA16 ? (lane >> 4) : (lane >> 5);
+  const int a_rd = (wm * WM + lrow) * 128;
+  const int b_rd = BM * 128 + (wn * WN + lrow) * 128;
+  const int sw = (lrow >> 1) & 7;
 
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -264,6 +353,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
+  constexpr bool MFMA16 = use_mfma16<NWAVES>();
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
   static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
   static_assert(NWAVES * CHUNK_BYTES <= STAGE_BYTES, "the epilogue chunks live in the idle stage buffer");
@@ -271,7 +361,6 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N;
-  const int l31 = lane & 31, lhi = lane >> 5;
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
@@ -279,32 +368,36 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= 2 * g.hidden) {
-      // v columns (the whole workgroup: 2*hidden is a multiple of BN).  Untransposed blocks: lane =
-      // column n = one v dimension, registers = rows (tokens); written as rows of the transposed
-      // v buffer, 64 tokens of one dimension per chunk row.
-      float bv[TN];
+      // v columns (the whole workgroup: 2*hidden is a multiple of BN).  Untransposed blocks: a lane's
+      // group holds one v dimension n (the block "row" here) and four consecutive tokens; written as
+      // rows of the transposed v buffer, 64 tokens of one dimension per chunk row.  With the roles of
+      // the operands swapped the two halves of a 16x16x32 group index swap too (vsub).
+      float bv[TN][4];
       main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int n = n0 + wn * WN + j * 32 + l31;
-          bv[j] = (g.bias && n < N) ? g.bias[n] : 0.f;
-        }
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = n0 + wn * WN + j * 32 + blk_row<MFMA16>(q, lane);
+            bv[j][q] = (g.bias && n < N) ? g.bias[n] : 0.f;
+          }
       });
       const bool wide = (g.ld_vt & 7) == 0;
       const bool wt_v = lines_exclusive(g.vt, g.ld_vt * 2);   // a workgroup writes 512-byte runs of a v^T row
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const float b = bv[j];
 #pragma unroll
         for (int i = 0; i < TM; i += 2) {
           f32x4 v[2][4];
 #pragma unroll
           for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < 4; ++q) {
+              const int vsub = MFMA16 ? (((q & 1) << 1) | (q >> 1)) : q;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * q + e] + b;
-          store_block<2, bf16_t, false>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
+              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * vsub + e] + bv[j][q];
+            }
+          store_block<2, bf16_t, false, MFMA16>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
                                         N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide, wt_v);
         }
       }
@@ -340,14 +433,16 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   };
   // The bias of the lane's columns is fetched there too (a load inside the epilogue waits out its
   // latency once per chunk).
-  f32x4 bias_r[TN][4];
-  [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][4];
+  // (with the 16x16x32 shape groups q and q + 2 hold the same columns: two distinct column groups per block)
+  constexpr int CQ = MFMA16 ? 2 : 4;
+  f32x4 bias_r[TN][CQ];
+  [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][CQ];
   main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * WN + 4 * lhi + j * 32 + 8 * q;
+      for (int q = 0; q < CQ; ++q) {
+        const int n = n0 + wn * WN + j * 32 + blk_col<MFMA16>(q, lane);
         bias_r[j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (g.bias && n < N) bias_r[j][q] = *reinterpret_cast<const f32x4*>(g.bias + n);
         if constexpr (EPI == EPI_RESADD_SCALED_F32) {
@@ -395,9 +490,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   }
 
   // ---- epilogue.  Register 4q+e of lane l in block (i,j) is the element
-  //      (row m = i*32 + l%32, column n = j*32 + 8q + 4*(l/32) + e).
+  //      (row m = i*32 + blk_row(q, l), column n = j*32 + blk_col(q, l) + e).
   const int nw = n0 + wn * WN;               // first column of this wave
-  const int nl = nw + 4 * lhi;               // first column this lane holds
   const bool wide = (g.ldo & 7) == 0;
   // write-through stores only where no 128-byte line of the output is shared with another workgroup:
   // aligned rows, and a tile's column extent in bytes a multiple of 128
@@ -406,13 +500,13 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   const bool wt = TILE_OUT_BYTES % 128 == 0 && lines_exclusive(g.out, g.ldo * OUT_ES);
   // QKV: byte offset of the first (cos, sin) pair of every 4-column group, once per lane (the
   // divisions by run-time sizes must not be redone for every row block)
-  [[maybe_unused]] int rope_off[TN][4];
+  [[maybe_unused]] int rope_off[TN][CQ];
   if constexpr (EPI == EPI_QKV) {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = nl + j * 32 + 8 * q;
+      for (int q = 0; q < CQ; ++q) {
+        const int n = nw + j * 32 + blk_col<MFMA16>(q, lane);
         rope_off[j][q] = ((((n < g.hidden ? n : n - g.hidden)) % g.head_dim) >> 1) * 8;
       }
   }
@@ -430,11 +524,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int j = 2 * (p0 + b);
-            const f32x4 bg = bias_r[j][q], bu = bias_r[j + 1][q];
+            const f32x4 bg = bias_r[j][q % CQ], bu = bias_r[j + 1][q % CQ];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[b][q][e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
           }
-        store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M,
+        store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M,
                                        (nw >> 1) + p0 * 32, N >> 1, wide, wt);
       };
       constexpr int NP = TN / 2;
@@ -451,12 +545,12 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int j = j0 + b;
-            const int n = nl + j * 32 + 8 * q;
+            const int n = nw + j * 32 + blk_col<MFMA16>(q, lane);
             f32x4 t;
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
-            t += bias_r[j][q];
-            if constexpr (EPI == EPI_RESADD_SCALED_F32) t *= scale_r[j][q];
+            t += bias_r[j][q % CQ];
+            if constexpr (EPI == EPI_RESADD_SCALED_F32) t *= scale_r[j][q % CQ];
             if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) t[e] = gelu_erf(t[e]);
@@ -464,7 +558,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             if constexpr (EPI == EPI_QKV) {
               // q and k columns: rotary on neighbouring columns (2p, 2p+1), both held by this lane
               if (g.rope_cs) {
-                const f32x4 cs = *reinterpret_cast<const f32x4*>(smem + (mrow - m0 + l31) * rope_stride + rope_off[j][q]);  // cos,sin,cos,sin
+                const f32x4 cs = *reinterpret_cast<const f32x4*>(smem + (mrow - m0 + blk_row<MFMA16>(q, lane)) * rope_stride + rope_off[j][q % CQ]);  // cos,sin,cos,sin
                 const float r0 = t[0] * cs[0] - t[1] * cs[1], r1 = t[1] * cs[0] + t[0] * cs[1];
                 const float r2 = t[2] * cs[2] - t[3] * cs[3], r3 = t[3] * cs[2] + t[2] * cs[3];
                 t[0] = r0; t[1] = r1; t[2] = r2; t[3] = r3;
@@ -475,18 +569,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
           }
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
-          store_block<NB, float, true>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, false,
-                                       HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
+          store_block<NB, float, true, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true,
+                                       wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
           if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
           }
         } else if constexpr (OUT_F32) {
-          store_block<NB, float, false>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, wt);
+          store_block<NB, float, false, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, wt);
         } else if constexpr (EPI == EPI_QKV) {
-          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0,
+          store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0,
                                          2 * g.hidden, wide, wt);
         } else {
-          store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide, wt);
+          store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide, wt);
           if constexpr (EPI == EPI_GELU_SPLIT) {
             // second half of the row: what the bf16 rounding of the first half dropped
 #pragma unroll
@@ -496,7 +590,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
                 const bf16x4 h = __builtin_convertvector(v[b][q], bf16x4);
                 v[b][q] -= __builtin_convertvector(h, f32x4);
               }
-            store_block<NB, bf16_t, false>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, N,
+            store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, N,
                                            wide && (N & 7) == 0, wt && (N & 63) == 0);
           }
         }
@@ -647,6 +741,11 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // (the scaled residual epilogue spills registers with eight waves and with 160-wide wave tiles: it
   // takes the 256 x 128 or 128 x 128 tiles)
   constexpr bool EIGHT_WAVES_OK = EPI != EPI_RESADD_SCALED_F32;
+#ifdef CS_GEMM_FORCE_256      // measurement build: the 256 x 256 tile whatever the number of workgroups
+  if constexpr (EIGHT_WAVES_OK) {
+    if (big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+  }
+#endif
   if constexpr (EIGHT_WAVES_OK) {
     // 256 x 256 for a round and a half of the chip or more
     if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
