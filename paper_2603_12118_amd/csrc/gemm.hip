@@ -138,13 +138,18 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
 #ifndef CS_GEMM_RESADD_WT     // 1: the residual-add epilogue stores write-through like the others
 #define CS_GEMM_RESADD_WT 1
 #endif
+#ifndef CS_GEMM_NARROW8       // the 256 x 160 tile with eight waves of 64 x 80: 0 never, 1 for long K loops, 2 always
+#define CS_GEMM_NARROW8 0
+#endif
 #ifndef CS_GEMM_A_AUX
 #define CS_GEMM_A_AUX 0
 #endif
 
 // Issues the LDS-direct loads of one 64-wide K slice: every wave instruction moves 64 x 16 bytes
 // from the lanes' global addresses to 1 KB of LDS starting at a wave-uniform address, in lane order.
-template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
+// (A wave whose share of the W rows lies beyond the tile, where BN is not a multiple of 8 rows per wave,
+// skips that load: wave-uniform.)
+template <int A_LOADS, int B_LOADS, int NWAVES, int BM, int BN>
 __device__ __forceinline__ void issue_slice(const bf16_t* const* ap, const bf16_t* const* bp, int kt,
                                             unsigned char* stage, int wave) {
 #pragma unroll
@@ -152,16 +157,17 @@ __device__ __forceinline__ void issue_slice(const bf16_t* const* ap, const bf16_
     __builtin_amdgcn_global_load_lds(ap[i] + kt * 64, (lds_void*)(uintptr_t)(stage + (i * NWAVES + wave) * 1024), 16, 0, CS_GEMM_A_AUX);
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i)
+    if (BN % (8 * NWAVES) == 0 || (i * NWAVES + wave) * 8 < BN)
     __builtin_amdgcn_global_load_lds(bp[i] + kt * 64, (lds_void*)(uintptr_t)(stage + BM * 128 + (i * NWAVES + wave) * 1024), 16, 0, CS_GEMM_W_AUX);
 }
 
 // One of the A_LOADS + B_LOADS loads of a slice, by index.
-template <int A_LOADS, int B_LOADS, int NWAVES, int BM>
+template <int A_LOADS, int B_LOADS, int NWAVES, int BM, int BN>
 __device__ __forceinline__ void issue_one(const bf16_t* const* ap, const bf16_t* const* bp, int l, int kt,
                                           unsigned char* stage, int wave) {
   if (l < A_LOADS)
     __builtin_amdgcn_global_load_lds(ap[l] + kt * 64, (lds_void*)(uintptr_t)(stage + (l * NWAVES + wave) * 1024), 16, 0, CS_GEMM_A_AUX);
-  else
+  else if (BN % (8 * NWAVES) == 0 || ((l - A_LOADS) * NWAVES + wave) * 8 < BN)
     __builtin_amdgcn_global_load_lds(bp[l - A_LOADS] + kt * 64,
                                      (lds_void*)(uintptr_t)(stage + BM * 128 + ((l - A_LOADS) * NWAVES + wave) * 1024), 16, 0, CS_GEMM_W_AUX);
 }
@@ -174,11 +180,11 @@ __device__ __forceinline__ void issue_one(const bf16_t* const* ap, const bf16_t*
 template <int BM, int BN, int WGM, int WGN, bool W_FIRST, bool PREFETCH>
 __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* const* bp, int kn,
                                         const unsigned char* cur, unsigned char* nxt, int a_rd, int b_rd, int sw,
-                                        int lhi, int wave, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
-  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+                                        int lhi, int wave, f32x16 (&acc)[BM / WGM / 32][(BN / WGN + 31) / 32]) {
+  constexpr int TM = BM / WGM / 32, TN = (BN / WGN + 31) / 32;
   constexpr int NWAVES = WGM * WGN;
   constexpr bool MFMA16 = use_mfma16<NWAVES>();
-  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
+  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = (BN + 8 * NWAVES - 1) / (8 * NWAVES);
   constexpr int RD_PER = 2;     // LDS reads of the next k-step issued behind each of the first MFMAs
   constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
   if constexpr (MFMA16) {
@@ -189,7 +195,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
     // k-step's come in behind the first MFMAs); the other is streamed through a ring of four registers
     // sets, each fragment requested three rows of MFMAs before its turn, so 48 registers hold the operands
     // whatever the wave tile (a full double buffer of a 128 x 64 tile would take 96).
-    constexpr int TM16 = 2 * TM, TN16 = 2 * TN;
+    constexpr int TM16 = 2 * TM, TN16 = BN / WGN / 16;   // a wave's columns may end in the middle of its last 32-block
     constexpr bool STREAM_A = TM16 >= TN16;
     constexpr int NO = STREAM_A ? TM16 : TN16;      // streamed fragments per k-step
     constexpr int NI = STREAM_A ? TN16 : TM16;      // held fragments per k-step
@@ -223,7 +229,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
           constexpr int LT = A_LOADS + B_LOADS, SLOTS = NO * NI;
 #pragma unroll
           for (int l = 0; l < LT; ++l)
-            if (l * SLOTS / LT == n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
+            if (l * SLOTS / LT == n) issue_one<A_LOADS, B_LOADS, NWAVES, BM, BN>(ap, bp, l, kn, nxt, wave);
         }
         if (in == 0 && r + 3 < 2 * NO) sf[(r + 3) & 3] = read_streamed(r + 3);
         if (ks == 0 && n < NI) hf[1][n] = *reinterpret_cast<const bf16x8*>(cur + h_rd + n * 16 * 128 + coff1);
@@ -257,7 +263,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
         constexpr int LT = A_LOADS + B_LOADS, SLOTS = SPREAD_KS * TM * TN;
 #pragma unroll
         for (int l = 0; l < LT; ++l)
-          if (l * SLOTS / LT == ks * TM * TN + n) issue_one<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, l, kn, nxt, wave);
+          if (l * SLOTS / LT == ks * TM * TN + n) issue_one<A_LOADS, B_LOADS, NWAVES, BM, BN>(ap, bp, l, kn, nxt, wave);
       }
       if (ks < 3) {
 #pragma unroll
@@ -278,14 +284,15 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
 // are in flight while those execute.
 template <int BM, int BN, int WGM, int WGN, bool W_FIRST, typename F>
 __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem, int m0, int n0,
-                                          f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], F&& before_last) {
+                                          f32x16 (&acc)[BM / WGM / 32][(BN / WGN + 31) / 32], F&& before_last) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
-  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int TM = WM / 32, TN = (WN + 31) / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
   constexpr bool MFMA16 = use_mfma16<NWAVES>();
-  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = BN / (8 * NWAVES);
-  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile vs waves");
+  constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = (BN + 8 * NWAVES - 1) / (8 * NWAVES);
+  static_assert(BM % (8 * NWAVES) == 0 && BN % 8 == 0, "tile vs waves");
+  static_assert(WM % 32 == 0 && WN % (MFMA16 ? 16 : 32) == 0, "wave tile vs MFMA shape");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N, K = g.K;
@@ -321,7 +328,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
     bp[i] = g.W + (int64_t)r * g.ldw + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
   }
   const int KT = K >> 6;
-  issue_slice<A_LOADS, B_LOADS, NWAVES, BM>(ap, bp, 0, smem, wave);
+  issue_slice<A_LOADS, B_LOADS, NWAVES, BM, BN>(ap, bp, 0, smem, wave);
   for (int kt = 0; kt < KT - 1; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
     unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
@@ -350,10 +357,11 @@ constexpr bool light_tail() {
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
-  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int TM = WM / 32, TN = (WN + 31) / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
   constexpr bool MFMA16 = use_mfma16<NWAVES>();
+  static_assert((EPI != EPI_SWIGLU_BF16 && EPI != EPI_QKV) || WN % 32 == 0, "these epilogues work on whole 32-column blocks");
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
   static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
   static_assert(NWAVES * CHUNK_BYTES <= STAGE_BYTES, "the epilogue chunks live in the idle stage buffer");
@@ -492,6 +500,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // ---- epilogue.  Register 4q+e of lane l in block (i,j) is the element
   //      (row m = i*32 + blk_row(q, l), column n = j*32 + blk_col(q, l) + e).
   const int nw = n0 + wn * WN;               // first column of this wave
+  const int n_end = nw + WN < N ? nw + WN : N;   // one past its last (the wave's last 32-block may be half used)
   const bool wide = (g.ldo & 7) == 0;
   // write-through stores only where no 128-byte line of the output is shared with another workgroup:
   // aligned rows, and a tile's column extent in bytes a multiple of 128
@@ -569,18 +578,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
           }
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
-          store_block<NB, float, true, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true,
+          store_block<NB, float, true, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
                                        wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
           if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
           }
         } else if constexpr (OUT_F32) {
-          store_block<NB, float, false, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, true, wt);
+          store_block<NB, float, false, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true, wt);
         } else if constexpr (EPI == EPI_QKV) {
           store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0,
                                          2 * g.hidden, wide, wt);
         } else {
-          store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, N, wide, wt);
+          store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, wide, wt);
           if constexpr (EPI == EPI_GELU_SPLIT) {
             // second half of the row: what the bf16 rounding of the first half dropped
 #pragma unroll
@@ -590,7 +599,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
                 const bf16x4 h = __builtin_convertvector(v[b][q], bf16x4);
                 v[b][q] -= __builtin_convertvector(h, f32x4);
               }
-            store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, N,
+            store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out) + N, g.ldo, g.row_map, mrow, M, col0, n_end,
                                            wide && (N & 7) == 0, wt && (N & 63) == 0);
           }
         }
@@ -754,7 +763,16 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
     // workgroups, one round of the chip at M = 8192
     if constexpr (EIGHT_WAVES_OK) {
-      if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+      if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) {
+#if CS_GEMM_NARROW8 && CS_GEMM_MFMA16
+        // eight waves of 64 x 80 (16x16x32 MFMAs, the wave's third 32-column block half used) where the K
+        // loop is long: their main loop is 8 % faster, but with two waves per SIMD the residual epilogue can
+        // prefetch only one row block of x at a time, which costs more than that at K = 1280 (measured:
+        // K = 3456 74 -> 71 us, K = 1280 36.4 -> 37.5 us)
+        if (CS_GEMM_NARROW8 == 2 || g.K >= 2560) return launch_cfg<256, 160, 4, 2, EPI>(g, stream);
+#endif
+        return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
+      }
     }
     // the same for N = 1024: 256 x 128 tiles
     if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
