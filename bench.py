@@ -14,12 +14,33 @@ import time
 
 import numpy as np
 
+import hashlib
+import os
+import re
+
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 2.4 GHz x 4096 flop/CU/clk, dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per launch of the gate|up GEMM on c2_images from the FETCH_SIZE / WRITE_SIZE counter
-# runs summarised in profiles/c2_images_hbm_counters.md: (109925 KiB x 2.00 + 55296 KiB x 1.00) x 1024.
-# Valid for the kernel those counters were taken on; set to None when gemm.hip changes.
-GATE_UP_TRAFFIC_BYTES = {"c2_images": (109925 * 2.00 + 55296 * 1.00) * 1024}
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+
+def measured_traffic(workload: str, kernel: str, items_default: bool):
+    """HBM-side bytes per launch of the dominant kernel, from the counter summary profiles/<workload>_hbm_counters.md
+    (lines `dominant_kernel: ...`, `dominant_kernel_traffic_bytes: ...`, `gemm_hip_sha256: ...`).  The counters
+    belong to the kernel source and launch they were taken on: None when the summary is missing, when gemm.hip
+    has changed since, when the batch is not the workload's own, or when another kernel instantiation runs now."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_counters.md")
+    if not items_default or not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    m = {k: re.search(rf"^{k}:\s*(.+)$", text, re.M) for k in ("dominant_kernel", "dominant_kernel_traffic_bytes", "gemm_hip_sha256")}
+    if not all(m.values()):
+        return None, None
+    src = os.path.join(ROOT, "paper_2603_12118_amd", "csrc", "gemm.hip")
+    if hashlib.sha256(open(src, "rb").read()).hexdigest() != m["gemm_hip_sha256"].group(1).strip():
+        return None, "gemm.hip changed since profiles/%s_hbm_counters.md was taken" % workload
+    if m["dominant_kernel"].group(1).strip() != kernel:
+        return None, "the counters were taken on another kernel instantiation"
+    return float(m["dominant_kernel_traffic_bytes"].group(1)), "profiles/%s_hbm_counters.md" % workload
 
 
 def algorithmic_flops(cfg, grid_thw) -> dict:
@@ -127,15 +148,33 @@ def main() -> int:
     # pair idles the stream for about 5 us on either side of the launch, 0.36 ms per step if all 32 are timed
     enc.cs_encoder_time_step(B.STEPS[dominant])
     enc.cs_encoder_time_every(8)
+    # the K timed steps: wall clock between two synchronisations (`value`), and beside it a HIP event between
+    # every two steps on the stream the kernels run on (torch's current stream) for the median step
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    evs[0].record()
+    for i in range(args.steps):
         step()
+        evs[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
+    ev_ms = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
     dom_ms, dom_n = enc.cs_encoder_read_timing()
     enc.cs_encoder_time_step(0)
     enc.cs_encoder_time_every(1)
+
+    # host side of one call: time of the cs_encode + cs_forward_embeddings calls themselves (plan lookup,
+    # validation, launches), the stream idle before each
+    host_us = []
+    for _ in range(10):
+        torch.cuda.synchronize()
+        th = time.perf_counter()
+        step()
+        host_us.append((time.perf_counter() - th) * 1e6)
+    torch.cuda.synchronize()
+    host_us.sort()
+    plan_hits, plan_misses = enc.cs_encoder_plan_cache_stats()
 
     fl = algorithmic_flops(w.cfg, w.grid_thw)
     n_in = int(w.cu_seqlens[-1])
@@ -145,20 +184,24 @@ def main() -> int:
     dom_flops = fl[dominant] / w.cfg.n_layers
     dom_tflops = dom_flops / (dom_avg_ms * 1e-3) / 1e12
 
+    kernel = enc.cs_encoder_step_kernel(B.STEPS[dominant], int(w.cu_seqlens[-1]) // (2 if w.cfg.arch == "audio" else 1))
+    traffic, traffic_src = measured_traffic(w.name, kernel, args.items <= 0)
     res = {
         "metric": "encoder_patches_per_s" if w.cfg.arch != "audio" else "encoder_mel_frames_per_s",
         "value": n_in / (ms * 1e-3), "unit": "patches/s" if w.cfg.arch != "audio" else "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "ms_per_step_median_hip_events": ev_ms[len(ev_ms) // 2], "ms_per_step_min_hip_events": ev_ms[0],
+        "host_us_per_call_median": host_us[len(host_us) // 2], "plan_cache": {"hits": plan_hits, "misses": plan_misses},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "items": w.n_items, "input_rows": n_in, "embedding_rows": int(n_out),
                    "layers": w.cfg.n_layers, "hidden": w.cfg.hidden, "out_hidden": w.cfg.out_hidden},
         "items_per_s": w.n_items / (ms * 1e-3),
         "algorithmic_tflop_per_step": fl["total"] / 1e12,
         "achieved_tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
-        "roofline": {"kernel": "gemm_kernel<256,256,2,4,SWIGLU> (gate|up projection)" if w.cfg.arch == "vit"
-                     else "gemm_kernel<256,256,2,4,GELU> (fc1)", "bound": "mfma",
+        "roofline": {"kernel": kernel + (" (gate|up projection + SwiGLU)" if w.cfg.arch == "vit" else " (fc1 + GELU)"),
+                     "bound": "mfma",
                      "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": GATE_UP_TRAFFIC_BYTES.get(w.name),
+                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                      "avg_launch_ms": dom_avg_ms, "launches_timed": dom_n, "flop_per_launch": dom_flops},
         "setup_s": setup_s,
     }

@@ -367,6 +367,10 @@ typedef enum {
   CS_STEP_BACK = 9         /* final norm, merger / pooling, output projection       */
 } cs_step;
 cs_status cs_encoder_time_step(cs_encoder* enc, int32_t step);
+/* Host-only measurement aid: the name of the GEMM kernel instantiation (tile, waves, epilogue, tail handling,
+ * MFMA shape) that `step` (CS_STEP_QKV, CS_STEP_PROJ, CS_STEP_MLP_UP or CS_STEP_MLP_DOWN) runs for a batch of
+ * n_tokens tokens when it is not split over K, written as a C string to `out` (capacity >= 96). */
+cs_status cs_encoder_step_kernel(const cs_encoder* enc, int32_t step, int64_t n_tokens, char* out, size_t capacity);
 /* An event pair costs the stream about 5 us of idle time on either side of the launch it brackets
  * (measured: 0.36 ms per step when all 32 launches of one step are timed).  cs_encoder_time_every(enc, n)
  * times only every n-th launch of the selected step (n >= 1; default 1), counted from the call. */

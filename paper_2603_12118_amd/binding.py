@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
         L.cs_xchannel_describe.argtypes = [vp, C.c_int32, i32p, C.POINTER(vp), C.POINTER(i64), i32p, i32p,
                                            C.POINTER(i64), C.POINTER(i64)]
         L.cs_mfma_ceiling.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
+        L.cs_encoder_step_kernel.argtypes = [vp, C.c_int32, i64, C.c_char_p, C.c_size_t]
         L.cs_encoder_time_step.argtypes = [vp, C.c_int32]
         L.cs_encoder_time_every.argtypes = [vp, C.c_int32]
         L.cs_encoder_read_timing.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -96,7 +97,7 @@ def lib() -> C.CDLL:
         L.cs_last_error.restype = C.c_char_p
         for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encode_static", "cs_encoder_plan_cache_stats",
                   "cs_forward_embeddings", "cs_plan_tokens",
-                  "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_time_every",
+                  "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_step_kernel", "cs_encoder_time_every",
                   "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
                   "cs_channel_acquire", "cs_channel_publish", "cs_channel_forward", "cs_channel_release",
                   "cs_channel_describe", "cs_xchannel_create", "cs_xchannel_open", "cs_xchannel_acquire",
@@ -188,6 +189,11 @@ class Encoder:
 
     def cs_encoder_time_step(self, step: int) -> None:
         _check(lib().cs_encoder_time_step(self._h, step))
+
+    def cs_encoder_step_kernel(self, step: int, n_tokens: int) -> str:
+        buf = C.create_string_buffer(128)
+        _check(lib().cs_encoder_step_kernel(self._h, step, n_tokens, buf, 128))
+        return buf.value.decode()
 
     def cs_encoder_time_every(self, every: int) -> None:
         _check(lib().cs_encoder_time_every(self._h, every))

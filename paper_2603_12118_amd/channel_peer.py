@@ -9,8 +9,10 @@ Producer commands: create {n_slots, slot_bytes} | acquire {nbytes} | publish {sl
 the producer's stream, after `busy` rounds of unrelated work on that stream) | publish_raw {slot, n, hidden}
 (publishes whatever the slot holds) | release {slot} | describe {slot} | quit.
 Consumer commands: open | buffers {count, rows, hidden, seed} | wait {timeout_us} | forward {slot, dst, index}
-| describe {slot} | settle {slot, timeout_us} (polls until the slot is FREE) | dump {path} (buffers as .npy)
-| flag | quit.
+| stage_index {index} (uploads placeholder positions ahead of the tensor, as a consumer that knows where its
+placeholders are does) | wait_forward {timeout_us, dst} (waits for the next tensor and places it with the staged
+index, one command: what a serving consumer does) | describe {slot} | settle {slot, timeout_us} (polls until the
+slot is FREE) | dump {path} (buffers as .npy) | flag | quit.
 """
 from __future__ import annotations
 
@@ -40,7 +42,7 @@ def main(role: str, name: str) -> int:
     ch = None
     bufs, flag = [], torch.zeros(1, dtype=torch.int32, device=dev)
     ballast = torch.randn(1024, 1024, device=dev)
-    keep = []
+    keep, staged = [], None
     torch.cuda.synchronize()
     out = sys.stdout
     print(json.dumps({"ready": role}), file=out, flush=True)
@@ -93,6 +95,14 @@ def main(role: str, name: str) -> int:
             torch.cuda.current_stream().synchronize()
             keep.append(idx)
             r = {"st": ch.cs_xchannel_forward(c["slot"], idx, bufs[c["dst"]], flag, stream)}
+        elif op == "stage_index":
+            staged = torch.tensor(c["index"], dtype=torch.int64, device=dev)
+            torch.cuda.synchronize()
+        elif op == "wait_forward":
+            st, slot, rows, hidden, dtype = ch.cs_xchannel_wait(c["timeout_us"])
+            r = {"st": st, "slot": slot, "n": rows}
+            if st == 0:
+                r["st_forward"] = ch.cs_xchannel_forward(slot, staged[:rows], bufs[c["dst"]], flag, stream)
         elif op == "settle":
             t0, state = time.perf_counter(), -1
             while (time.perf_counter() - t0) * 1e6 < c["timeout_us"]:

@@ -681,6 +681,41 @@ cs_status cs_encoder_read_timing(cs_encoder* enc, double* total_ms, int64_t* lau
   return CS_OK;
 }
 
+cs_status cs_encoder_step_kernel(const cs_encoder* enc, int32_t step, int64_t n_tokens, char* out, size_t capacity) {
+  if (!enc || !out || capacity < 96 || n_tokens <= 0 || n_tokens > 0x7fffffff)
+    return fail(CS_ERR_INVALID_ARG, "cs_encoder_step_kernel: NULL argument, capacity below 96 or bad token count");
+  const cs_encoder_config& c = enc->cfg;
+  const int64_t D = c.hidden;
+  GemmArgs g = {};
+  g.describe = out;
+  g.M = (int32_t)n_tokens;
+  int epi = EPI_BF16;
+  switch (step) {
+    case CS_STEP_QKV:
+      g.N = (int32_t)(3 * D); g.K = (int32_t)D; g.ldo = 2 * D; g.hidden = (int32_t)D; g.head_dim = c.head_dim; g.ld_vt = round_up(n_tokens, 64);
+      g.M = (int32_t)round_up(n_tokens, 4);
+      epi = EPI_QKV;
+      break;
+    case CS_STEP_PROJ:
+      g.N = (int32_t)D; g.K = (int32_t)D; g.ldo = D;
+      epi = c.arch == CS_ARCH_VIT_CLS ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32;
+      break;
+    case CS_STEP_MLP_UP:
+      g.N = c.arch == CS_ARCH_VIT ? 2 * enc->I_pad : enc->I_pad; g.K = (int32_t)D; g.ldo = enc->I_pad;
+      epi = c.arch == CS_ARCH_VIT ? EPI_SWIGLU_BF16 : EPI_GELU_BF16;
+      break;
+    case CS_STEP_MLP_DOWN:
+      g.N = (int32_t)D; g.K = enc->I_pad; g.ldo = D;
+      epi = c.arch == CS_ARCH_VIT_CLS ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32;
+      break;
+    default: return fail(CS_ERR_INVALID_ARG, "cs_encoder_step_kernel: step must be one of the four GEMM steps of a block");
+  }
+  g.lda = g.K;
+  if (epi == EPI_RESADD_SCALED_F32) g.col_scale = enc->ptr<float>(enc->layers[0].ls1);
+  // (batches small enough for split K run other launches; this names the kernel of the unsplit path)
+  return launch_gemm(epi, g, nullptr);
+}
+
 cs_status cs_encoder_query(const cs_encoder* enc, const int32_t* cu_seqlens, const int32_t* grid_thw, int32_t n_items,
                            int64_t* n_out_rows, size_t* workspace_bytes) {
   if (!enc) return fail(CS_ERR_INVALID_ARG, "cs_encoder_query: NULL encoder");

@@ -59,6 +59,9 @@ struct GemmArgs {
   int32_t hidden;    // q columns [0,hidden), k [hidden,2 hidden), v [2 hidden, 3 hidden)
   int32_t head_dim;
   float q_scale;
+  // measurement aid: when set (host buffer of at least 96 bytes), launch_gemm writes the name of the kernel
+  // instantiation it would run for these arguments there and launches nothing
+  char* describe;
 };
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);

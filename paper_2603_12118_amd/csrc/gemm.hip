@@ -18,6 +18,7 @@
 // columns in groups of four consecutive n: bias, activations, rotary pairs and 8/16-byte stores
 // all work on registers of one lane.  Inside a K slice the LDS reads of k-step s+1 are issued
 // behind the first MFMAs of k-step s and scheduling barriers pin that order.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <atomic>
@@ -709,6 +710,11 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int LDS = 2 * (BM + BN) * 128;
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
+  if (g.describe) {
+    snprintf(g.describe, 96, "gemm_kernel<%d, %d, %d, %d, %d, %d>%s", BM, BN, WGM, WGN, EPI, TAIL,
+             use_mfma16<WGM * WGN>() ? " 16x16x32" : " 32x32x16");
+    return CS_OK;
+  }
   // one attribute call per instantiation (two threads that both see `false` repeat a harmless call)
   static std::atomic<bool> attr_set{false};
   if (!attr_set.load(std::memory_order_acquire)) {

@@ -117,14 +117,17 @@ def _xchannel(sizes_mb, hidden, n=20):
         for mb in sizes_mb:
             rows = mb * (1 << 20) // (hidden * 2)
             idx = rng.permutation(4 * max_rows)[:rows].tolist()
+            call(cons, "stage_index", index=idx)      # the consumer knows its placeholder positions beforehand
             lat = []
             for i in range(n + 3):
                 a = call(prod, "acquire", nbytes=rows * hidden * 2)
                 assert a["st"] == 0, a
+                # the consumer is already waiting when the producer publishes
+                cons.stdin.write(J.dumps({"op": "wait_forward", "timeout_us": 10_000_000, "dst": 0}) + "\n")
+                cons.stdin.flush()
                 assert call(prod, "fill", slot=a["slot"], ptr=a["ptr"], n=rows, hidden=hidden)["st"] == 0
-                w = call(cons, "wait", timeout_us=10_000_000)
-                assert w["st"] == 0 and w["slot"] == a["slot"], w
-                assert call(cons, "forward", slot=w["slot"], dst=0, index=idx)["st"] == 0
+                w = call(cons)
+                assert w["st"] == 0 and w["slot"] == a["slot"] and w["st_forward"] == 0, w
                 assert call(cons, "settle", slot=w["slot"], timeout_us=10_000_000)["state"] == 0
                 d = call(cons, "describe", slot=w["slot"])
                 if i >= 3:
