@@ -919,6 +919,10 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
         aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_win_work); aa.n_work = p.n_win_work; aa.q_per_block = 64; aa.single_tile = p.win_single_tile;
       }
       if (cs_status st = launch_attention(aa, stream)) return st;
+      if (full && p.n_tail_work > 0) {   // the short last query blocks of the items, as 64-query work items
+        aa.work = reinterpret_cast<const AttnWork*>(plan + p.off_tail_work); aa.n_work = p.n_tail_work; aa.q_per_block = 64; aa.single_tile = 0;
+        if (cs_status st = launch_attention(aa, stream)) return st;
+      }
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);

@@ -44,6 +44,15 @@ static void push_work(std::vector<int32_t>& v, int q0, int q1, int kv0, int kv1)
   v.push_back(kv1);
 }
 
+// Query blocks of a full-attention segment: 256 queries per work item; a last block of at most 64 queries
+// goes to the tail list (64-query work items).
+static void push_full(std::vector<int32_t>& full, std::vector<int32_t>& tail, int q0, int q1, int kv0, int kv1) {
+  for (int q = q0; q < q1; q += 256) {
+    const int e = std::min(q + 256, q1);
+    push_work(e - q <= 64 && q > q0 ? tail : full, q, e, kv0, kv1);
+  }
+}
+
 cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const int32_t* grid, int32_t n_items,
                          BatchPlan& p) {
   if (cs_status st = check_batch(cu, grid, n_items)) return st;
@@ -55,7 +64,7 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
   p = BatchPlan();
   p.n_in = p.n_tok = N;
   p.n_out = p.n_groups = N / (mg * mg);
-  std::vector<int32_t> src_row, pos, out_row, win_work, full_work;
+  std::vector<int32_t> src_row, pos, out_row, win_work, full_work, tail_work;
   src_row.reserve(N);
   pos.reserve(3 * N);
   out_row.reserve(p.n_out);
@@ -93,7 +102,7 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
           }
         }
     const int item_end = (int)src_row.size();
-    for (int q = item_start; q < item_end; q += 256) push_work(full_work, q, std::min(q + 256, item_end), item_start, item_end);
+    push_full(full_work, tail_work, item_start, item_end, item_start, item_end);
     out_base += (int64_t)T * (h / mg) * (w / mg);
   }
   p.off_src_row = blob_section(p.blob, src_row.size());
@@ -106,8 +115,11 @@ cs_status build_vit_plan(const cs_encoder_config& cfg, const int32_t* cu, const 
   std::copy(win_work.begin(), win_work.end(), p.blob.begin() + p.off_win_work);
   p.off_full_work = blob_section(p.blob, full_work.size());
   std::copy(full_work.begin(), full_work.end(), p.blob.begin() + p.off_full_work);
+  p.off_tail_work = blob_section(p.blob, tail_work.size());
+  std::copy(tail_work.begin(), tail_work.end(), p.blob.begin() + p.off_tail_work);
   p.n_win_work = (int32_t)(win_work.size() / 4);
   p.n_full_work = (int32_t)(full_work.size() / 4);
+  p.n_tail_work = (int32_t)(tail_work.size() / 4);
   return CS_OK;
 }
 
@@ -138,7 +150,7 @@ cs_status build_cls_plan(const cs_encoder_config& cfg, int32_t n_positions, cons
   p.n_tok = n_tok;
   p.n_out = p.n_in / (mg * mg);
   p.n_groups = n_tok / 4;
-  std::vector<int32_t> src_row, pos, out_row, full_work;
+  std::vector<int32_t> src_row, pos, out_row, full_work, tail_work;
   src_row.reserve(n_tok);
   pos.reserve(n_tok);
   out_row.reserve(p.n_groups);
@@ -160,7 +172,7 @@ cs_status build_cls_plan(const cs_encoder_config& cfg, int32_t n_positions, cons
     pos.insert(pos.end(), 3, -2);    // padding
     out_row.push_back(-1);
     const int keys_end = start + h * w + 1, end = start + h * w + 4;
-    for (int q = start; q < end; q += 256) push_work(full_work, q, std::min(q + 256, end), start, keys_end);
+    push_full(full_work, tail_work, start, end, start, keys_end);
     out_base += (int64_t)(h / mg) * (w / mg);
   }
   auto put = [&](const std::vector<int32_t>& v) {
@@ -173,6 +185,8 @@ cs_status build_cls_plan(const cs_encoder_config& cfg, int32_t n_positions, cons
   p.off_out_row = put(out_row);
   p.off_full_work = put(full_work);
   p.n_full_work = (int32_t)(full_work.size() / 4);
+  p.off_tail_work = put(tail_work);
+  p.n_tail_work = (int32_t)(tail_work.size() / 4);
   return CS_OK;
 }
 

@@ -20,7 +20,10 @@ struct BatchPlan {
   size_t off_out_row = 0;   // [n_out]   output row of internal merged token j
   size_t off_win_work = 0;  // [n_win_work*4] AttnWork, one window (or 64-query slice of it) each
   size_t off_full_work = 0; // [n_full_work*4] AttnWork, 256-query blocks of whole items
-  int32_t n_win_work = 0, n_full_work = 0;
+  size_t off_tail_work = 0; // [n_tail_work*4] AttnWork of the full layers: last query blocks of at most 64 queries,
+                            // run by two-wave workgroups in a launch of their own (a 256-query workgroup for four
+                            // queries would still walk every key tile and cost the launch a round of the chip)
+  int32_t n_win_work = 0, n_full_work = 0, n_tail_work = 0;
   bool win_single_tile = false;  // no window has more than 64 tokens
   int32_t full_q_per_block = 256;   // queries per item of full_work: 256, or 64 when the segments are short chunks
   bool full_single_tile = false;    // no full_work item has more than 64 keys
