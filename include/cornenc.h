@@ -195,6 +195,24 @@ cs_status cs_encode(cs_encoder* enc, const void* patches, const int32_t* cu_seql
 cs_status cs_encode_static(cs_encoder* enc, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
                            int32_t n_items, void* out_embeddings, void* stream);
 
+/* A recorded cs_encode, for batches small enough that the gaps between their ~330 short kernels show (one
+ * to four 448 x 448 images): the launch sequence of one batch description on one set of buffers, captured
+ * once into an executable HIP graph and replayed with one call.
+ *  - create runs the batch once eagerly on `stream` (a stream of the caller's, not the default stream; it is
+ *    synchronised), then records the same launches from that stream and instantiates the graph.  Arguments
+ *    as for cs_encode.  The index tables stay in the workspace: patches, out_embeddings and the workspace
+ *    belong to the graph until it is destroyed (new pixel data is written into `patches` in place; the
+ *    workspace must not be used by anything else in between).  Allocates (the graph); the launches do not.
+ *  - launch replays it on `stream`; results are bit-identical to cs_encode on the same inputs.
+ *  - No memset node is recorded (the path clears memory with kernels only).
+ * Errors: as cs_encode, plus CS_ERR_HIP if capture or instantiation fails (nothing is left behind). */
+typedef struct cs_encode_graph cs_encode_graph;
+cs_status cs_encode_graph_create(cs_encoder* enc, const void* patches, const int32_t* cu_seqlens,
+                                 const int32_t* grid_thw, int32_t n_items, void* out_embeddings, void* workspace,
+                                 size_t workspace_bytes, void* stream, cs_encode_graph** out);
+cs_status cs_encode_graph_launch(cs_encode_graph* graph, void* stream);
+void cs_encode_graph_destroy(cs_encode_graph* graph);
+
 /* Host-only: how often a batch description was found in (hits) or added to (misses) the encoder's
  * plan cache since create, over cs_encoder_query, cs_encode and cs_encode_static.  Either may be NULL. */
 cs_status cs_encoder_plan_cache_stats(const cs_encoder* enc, int64_t* hits, int64_t* misses);

@@ -61,6 +61,10 @@ def lib() -> C.CDLL:
         L.cs_encoder_query.argtypes = [vp, i32p, i32p, C.c_int32, C.POINTER(i64), C.POINTER(C.c_size_t)]
         L.cs_encode.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp, C.c_size_t, vp]
         L.cs_encode_static.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp]
+        L.cs_encode_graph_create.argtypes = [vp, vp, i32p, i32p, C.c_int32, vp, vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.cs_encode_graph_launch.argtypes = [vp, vp]
+        L.cs_encode_graph_destroy.argtypes = [vp]
+        L.cs_encode_graph_destroy.restype = None
         L.cs_encoder_plan_cache_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
         L.cs_forward_embeddings.argtypes = [vp, vp, vp, i64, i64, C.c_int32, C.c_int32, vp, vp]
         L.cs_plan_tokens.argtypes = [C.POINTER(cs_encoder_config), i32p, i32p, C.c_int32, i32p, i32p, i32p, C.c_int32, i32p]
@@ -95,7 +99,8 @@ def lib() -> C.CDLL:
         L.cs_status_string.argtypes = [C.c_int]
         L.cs_status_string.restype = C.c_char_p
         L.cs_last_error.restype = C.c_char_p
-        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encode_static", "cs_encoder_plan_cache_stats",
+        for f in ("cs_encoder_create", "cs_encoder_query", "cs_encode", "cs_encode_static", "cs_encoder_plan_cache_stats", "cs_encode_graph_create",
+                  "cs_encode_graph_launch",
                   "cs_forward_embeddings", "cs_plan_tokens",
                   "cs_linear_bf16", "cs_attention_varlen", "cs_encoder_time_step", "cs_encoder_step_kernel", "cs_encoder_time_every",
                   "cs_encoder_read_timing", "cs_patchify", "cs_mfma_ceiling", "cs_pack_batch", "cs_channel_create",
@@ -234,10 +239,39 @@ class Encoder:
                                       _stream(stream)))
         return out
 
+    def cs_encode_graph_create(self, patches, cu_seqlens, grid_thw, out, workspace, stream):
+        """-> EncodeGraph replaying cs_encode(patches, ...) into `out` (all buffers stay bound to it)."""
+        cu, g = _i32(cu_seqlens), _i32(grid_thw)
+        h = C.c_void_p()
+        _check(lib().cs_encode_graph_create(self._h, patches.data_ptr(), _i32p(cu), _i32p(g), g.shape[0], out.data_ptr(),
+                                            workspace.data_ptr(), workspace.numel(), int(stream.cuda_stream), C.byref(h)))
+        return EncodeGraph(h, (patches, out, workspace))
+
     def cs_encoder_plan_cache_stats(self):
         hits, misses = C.c_int64(), C.c_int64()
         _check(lib().cs_encoder_plan_cache_stats(self._h, C.byref(hits), C.byref(misses)))
         return hits.value, misses.value
+
+
+class EncodeGraph:
+    """Owns a cs_encode_graph handle and keeps the tensors it is bound to alive."""
+
+    def __init__(self, handle, bound):
+        self._h, self._bound = handle, bound
+
+    def cs_encode_graph_launch(self, stream=None) -> None:
+        _check(lib().cs_encode_graph_launch(self._h, _stream(stream)))
+
+    def close(self) -> None:
+        if self._h:
+            lib().cs_encode_graph_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def cs_plan_tokens(cfg, cu_seqlens, grid_thw):

@@ -104,6 +104,7 @@ struct cs_encoder {
   hipEvent_t stage_ev[2] = {nullptr, nullptr};
   bool stage_used[2] = {false, false};
   int stage_next = 0;
+  bool capturing = false;            // a cs_encode_graph is being recorded: no timing events
   // optional per-step event timing
   int time_step = 0;
   int time_every = 1;                // of the launches of time_step, every time_every-th is timed
@@ -474,7 +475,7 @@ struct StepTimer {
   cs_encoder* e;
   hipStream_t stream;
   bool on;
-  StepTimer(cs_encoder* enc, int step, hipStream_t s) : e(enc), stream(s), on(enc->time_step == step) {
+  StepTimer(cs_encoder* enc, int step, hipStream_t s) : e(enc), stream(s), on(enc->time_step == step && !enc->capturing) {
     if (on) on = (e->time_seen++ % e->time_every) == 0;
     if (!on) return;
     if (e->ev_used + 2 > e->ev_pool.size()) {
@@ -775,7 +776,7 @@ cs_status cs_plan_tokens(const cs_encoder_config* config, const int32_t* cu_seql
 // tables outgrow them (blocks the device); without it such a batch is refused and nothing allocates.
 static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
                              int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
-                             void* stream_, bool may_grow, const char* who) {
+                             void* stream_, bool may_grow, const char* who, bool capturing = false) {
   if (!e || !patches || !out_embeddings || !workspace) return fail(CS_ERR_INVALID_ARG, std::string(who) + ": NULL argument");
   if ((reinterpret_cast<uintptr_t>(patches) | reinterpret_cast<uintptr_t>(out_embeddings) |
        reinterpret_cast<uintptr_t>(workspace)) & 15)
@@ -789,12 +790,13 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
   if (workspace_bytes < w.total)
     return fail(CS_ERR_WORKSPACE, std::string(who) + ": " + (may_grow ? "workspace" : "the static scratch") + " has " +
                                       std::to_string(workspace_bytes) + " bytes, this batch needs " + std::to_string(w.total));
-  if (!may_grow && p.blob.size() * 4 > std::min(e->stage_cap[0], e->stage_cap[1]))
+  if (!may_grow && !capturing && p.blob.size() * 4 > std::min(e->stage_cap[0], e->stage_cap[1]))
     return fail(CS_ERR_WORKSPACE, std::string(who) + ": the index tables of this batch exceed the staging slots");
   unsigned char* ws = static_cast<unsigned char*>(workspace);
 
-  // ---- index tables: host -> pinned slot -> workspace, one async copy
-  {
+  // ---- index tables: host -> pinned slot -> workspace, one async copy (a stream under capture replays
+  // launches only: the tables are already in the workspace from the eager call before the capture)
+  if (!capturing) {
     const int s = e->stage_next;
     e->stage_next ^= 1;
     const size_t bytes = p.blob.size() * 4;
@@ -987,6 +989,64 @@ cs_status cs_encode(cs_encoder* e, const void* patches, const int32_t* cu_seqlen
     return encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, workspace, workspace_bytes, stream,
                        true, "cs_encode");
   });
+}
+
+}  // extern "C"
+
+// A recorded cs_encode: the launches of one batch on one set of buffers as an executable HIP graph.
+struct cs_encode_graph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+extern "C" {
+
+cs_status cs_encode_graph_create(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
+                                 int32_t n_items, void* out_embeddings, void* workspace, size_t workspace_bytes,
+                                 void* stream_, cs_encode_graph** out) {
+  if (!out) return fail(CS_ERR_INVALID_ARG, "cs_encode_graph_create: NULL out");
+  *out = nullptr;
+  return guarded("cs_encode_graph_create", [&]() -> cs_status {
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (!stream) return fail(CS_ERR_INVALID_ARG, "cs_encode_graph_create: capture needs a stream of its own, not the default stream");
+    // one eager call: validates, puts the index tables into the workspace, sets the kernels' attributes
+    if (cs_status st = encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, workspace, workspace_bytes,
+                                   stream_, true, "cs_encode_graph_create"))
+      return st;
+    CS_HIP(hipStreamSynchronize(stream));
+    cs_encode_graph* g = new cs_encode_graph();
+    hipError_t he = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
+    if (he != hipSuccess) {
+      delete g;
+      return fail(CS_ERR_HIP, std::string("cs_encode_graph_create: hipStreamBeginCapture: ") + hipGetErrorString(he));
+    }
+    e->capturing = true;
+    const cs_status st = encode_impl(e, patches, cu_seqlens, grid_thw, n_items, out_embeddings, workspace, workspace_bytes,
+                                     stream_, false, "cs_encode_graph_create", true);
+    e->capturing = false;
+    he = hipStreamEndCapture(stream, &g->graph);    // always ended, also after a failed launch
+    if (st == CS_OK && he == hipSuccess) he = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (st != CS_OK || he != hipSuccess) {
+      if (g->graph) (void)hipGraphDestroy(g->graph);
+      delete g;
+      return st != CS_OK ? st : fail(CS_ERR_HIP, std::string("cs_encode_graph_create: ") + hipGetErrorString(he));
+    }
+    *out = g;
+    return CS_OK;
+  });
+}
+
+cs_status cs_encode_graph_launch(cs_encode_graph* g, void* stream) {
+  if (!g || !g->exec) return fail(CS_ERR_INVALID_ARG, "cs_encode_graph_launch: NULL graph");
+  CS_HIP(hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)));
+  return CS_OK;
+}
+
+void cs_encode_graph_destroy(cs_encode_graph* g) {
+  if (!g) return;
+  if (g->exec) (void)hipGraphExecDestroy(g->exec);
+  if (g->graph) (void)hipGraphDestroy(g->graph);
+  delete g;
 }
 
 cs_status cs_encode_static(cs_encoder* e, const void* patches, const int32_t* cu_seqlens, const int32_t* grid_thw,
