@@ -413,8 +413,9 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
 
 // ---- workspace layout -----------------------------------------------------------------------
 struct Workspace {
-  size_t plan, rope, x, xn, attn, qk, vt, big, parts, total;
-  int64_t ld_vt;
+  size_t plan, rope, x, xn, attn, qk, vt, big, parts, ss, total;
+  int64_t ld_vt, ss_stride;
+  int fold_proj, fold_down;   // column tiles of the two residual GEMMs when they fold the next RMSNorm (0: they do not)
   bool split_k;   // small batches: the residual GEMMs run split over K into `parts`
 };
 
@@ -432,6 +433,15 @@ static int k_parts(int64_t M, int64_t N, int64_t K) {
   for (int s = 2; s <= MAX_K_PARTS; ++s)
     if (kt % s == 0 && kt / s >= 4 && wgs * s <= 640) best = s;
   return best;
+}
+
+// Measurement switch: CS_NO_NORM_FOLD=1 in the environment keeps every RMSNorm a kernel of its own (read once).
+static bool fold_off() {
+  static const bool off = [] {
+    const char* v = getenv("CS_NO_NORM_FOLD");
+    return v && *v && *v != '0';
+  }();
+  return off;
 }
 
 static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
@@ -466,6 +476,13 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   size_t part = (size_t)N * D;
   if (c.arch != CS_ARCH_AUDIO) part = std::max(part, (size_t)p.n_groups * std::max<int64_t>(e->MH_pad, c.out_hidden));
   w.parts = take(w.split_k ? (size_t)MAX_K_PARTS * part * 4 : 0);
+  // RMSNorm folded into the GEMMs around it (vision tower, unsplit residual GEMMs): per-row partial sums of
+  // squares, one per column tile of the residual GEMM
+  w.ss_stride = round_up(N, 64);
+  const bool fold = c.arch == CS_ARCH_VIT && !w.split_k && !fold_off();
+  w.fold_proj = fold ? gemm_norm_fold_parts(N, D, D) : 0;
+  w.fold_down = fold ? gemm_norm_fold_parts(N, D, e->I_pad) : 0;
+  w.ss = take((w.fold_proj || w.fold_down) ? (size_t)8 * w.ss_stride * 4 : 0);
   w.total = off;
   return w;
 }
@@ -848,7 +865,18 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     const PendingSum a = take_pending();
     return launch_add_partials(x, a.parts, a.n_parts, a.stride, a.bias, a.scale, N, (int32_t)D, stream);
   };
-  auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K) -> cs_status {
+  // RMSNorm folded into the GEMMs on both sides (vision tower): the residual GEMM in front of a norm also writes
+  // xn = bf16(x * gain) and per-row sums of squares, the GEMM behind it scales its rows by 1 / rms.  folded > 0:
+  // xn and ss are in that state, with so many partial sums per row.
+  float* ss = reinterpret_cast<float*>(ws + w.ss);
+  int folded = 0;
+  auto consume_norm = [&](GemmArgs& g) {
+    if (!folded) return;
+    g.ss_in = ss; g.ss_parts = folded; g.ss_stride = w.ss_stride; g.norm_dim = (int32_t)D; g.norm_eps = c.norm_eps;
+    folded = 0;
+  };
+  auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K, size_t next_gain,
+                           int fold_parts) -> cs_status {
     GemmArgs g = {};
     g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D;
     const int S = w.split_k ? k_parts(N, D, K) : 1;
@@ -862,6 +890,10 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     }
     g.bias = e->ptr<float>(bias); g.out = x; g.K = (int32_t)K;
     if (scale) g.col_scale = e->ptr<float>(scale);
+    if (!scale && next_gain && fold_parts > 0) {
+      g.norm_gain = e->ptr<float>(next_gain); g.xg = xn; g.ld_xg = D; g.ss_out = ss; g.ss_stride = w.ss_stride;
+      folded = fold_parts;
+    }
     return launch_gemm(scale ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32, g, stream);
   };
 
@@ -895,7 +927,8 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
   AttnArgs aa = {};
   aa.qk = qk; aa.vt = vt; aa.ld_vt = w.ld_vt; aa.out = attn; aa.n_tok = (int32_t)N; aa.n_heads = c.n_heads; aa.head_dim = c.head_dim;
   const float q_scale = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
-  auto norm = [&](size_t gain, size_t bias) {
+  auto norm = [&](size_t gain, size_t bias) -> cs_status {
+    if (folded) return CS_OK;      // the residual GEMM in front has written xn and the sums of squares
     StepTimer tm(e, CS_STEP_NORM, stream);
     if (vit) return launch_rmsnorm(x, e->ptr<float>(gain), c.norm_eps, xn, N, (int32_t)D, stream, take_pending());
     return launch_layernorm(x, e->ptr<float>(gain), e->ptr<float>(bias), c.norm_eps, xn, N, (int32_t)D, stream, take_pending());
@@ -910,6 +943,7 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
       g.out = qk; g.ldo = 2 * D; g.M = (int32_t)N; g.N = (int32_t)(3 * D); g.K = (int32_t)D;
       g.vt = vt; g.ld_vt = w.ld_vt; g.rope_cs = e->rope ? rope_cs : nullptr;
       g.hidden = (int32_t)D; g.head_dim = c.head_dim; g.q_scale = q_scale;
+      consume_norm(g);
       if (cs_status st = launch_gemm(EPI_QKV, g, stream)) return st;
     }
     const bool full = !vit || c.window <= 0 || ((c.full_attn_layer_mask >> l) & 1);
@@ -928,17 +962,25 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);
-      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D)) return st;
+      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D, vit ? L.g2 : 0, w.fold_proj)) return st;
     }
     if (cs_status st = norm(L.g2, L.be2)) return st;
     {
       StepTimer tm(e, CS_STEP_MLP_UP, stream);
-      if (vit) { if (cs_status st = gemm(EPI_SWIGLU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, 2 * e->I_pad, D, nullptr)) return st; }
+      if (vit) {
+        GemmArgs g = {};
+        g.A = xn; g.lda = D; g.W = e->ptr<bf16_t>(L.w1); g.bias = e->ptr<float>(L.b1); g.out = big; g.ldo = e->I_pad;
+        g.M = (int32_t)N; g.N = 2 * e->I_pad; g.K = (int32_t)D;
+        consume_norm(g);
+        if (cs_status st = launch_gemm(EPI_SWIGLU_BF16, g, stream)) return st;
+      }
       else { if (cs_status st = gemm(EPI_GELU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, e->I_pad, D, nullptr)) return st; }
     }
     {
       StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
-      if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad)) return st;
+      // (the norm behind the last block is the merger's, which splits its output: a kernel of its own)
+      const size_t next_g1 = vit && l + 1 < c.n_layers ? e->layers[l + 1].g1 : 0;
+      if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad, next_g1, w.fold_down)) return st;
     }
   }
 

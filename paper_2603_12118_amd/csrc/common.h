@@ -59,12 +59,31 @@ struct GemmArgs {
   int32_t hidden;    // q columns [0,hidden), k [hidden,2 hidden), v [2 hidden, 3 hidden)
   int32_t head_dim;
   float q_scale;
+  // RMSNorm folded into the GEMMs on both sides of it (y = (x g / rms) W^T + b = (1/rms) ((x g) W^T) + b: a
+  // row scale commutes with the product, and bf16(x g) carries the same relative rounding as bf16(x g / rms)).
+  //  producer (EPI_RESADD_F32 on the four-wave 256 x 160 tile): with ss_out set, the epilogue also writes
+  //    xg[m, n] = bf16(x_new[m, n] * norm_gain[n]) and ss_out[(n0 / 160) * ss_stride + m] = the sum of
+  //    x_new[m, n]^2 over the tile's columns;
+  //  consumer (EPI_QKV, EPI_SWIGLU_BF16): with ss_in set, row m of A W^T is multiplied by
+  //    rsqrt(sum over ss_parts of ss_in[p * ss_stride + m] / norm_dim + norm_eps) before the bias is added.
+  const float* norm_gain;
+  bf16_t* xg;
+  int64_t ld_xg;
+  float* ss_out;
+  const float* ss_in;
+  int32_t ss_parts;
+  int64_t ss_stride;
+  int32_t norm_dim;
+  float norm_eps;
   // measurement aid: when set (host buffer of at least 96 bytes), launch_gemm writes the name of the kernel
   // instantiation it would run for these arguments there and launches nothing
   char* describe;
 };
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
+// Column tiles (= partial sums of squares per row) of a residual GEMM that can fold the next RMSNorm into its
+// epilogue for M rows and N columns, or 0 if that launch would not run on the tile that supports it.
+int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K);
 
 // ---- write-through global stores -----------------------------------------------------------
 // Every XCD has its own L2, and the end of a kernel writes back whatever is dirty in it before the

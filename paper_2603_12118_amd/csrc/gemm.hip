@@ -75,16 +75,26 @@ __device__ __forceinline__ float silu_f(float z) {
 // through a private 32-row LDS chunk and writes them out as whole 64- or 128-byte row segments,
 // 16 bytes per lane.  LDS serves one wave's instructions in order, so no wait is needed between a
 // chunk's writes and reads beyond keeping the compiler from reordering them.
+constexpr int EXTRA_LDS_BYTES = 1024 + 4 * 256 * 4;   // what a tile may use behind its two stage buffers
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
 // v[b][q] holds columns b*32 + blk_col(q) .. +3 of row blk_row(q) of a 32 x (NB*32) block.
 // The block's element (r, c) goes to out[rowmap(row0 + r) * ld + col0 + c] for row0 + r < row_end,
 // col0 + c < col_end (col_end - col0 a multiple of 4); ACCUM adds to what is there (fp32 only).
+// Producer side of a folded RMSNorm: what the residual epilogue writes beside the updated stream.
+struct NormFold {
+  bf16_t* xg;             // [*, ld_xg] bf16(x_new * gain)
+  int64_t ld_xg;
+  const float* gain_lds;  // gain of the tile's columns, staged in LDS; index = column - n0
+  int n0;
+  float ssacc[4];         // this lane's sums of x_new^2, one per 8-row group of the 32-row block
+};
+
 template <int NB, typename T, bool ACCUM, bool MFMA16>
 __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&v)[NB][4], T* out, int64_t ld,
                                             const int32_t* row_map, int row0, int row_end, int col0, int col_end,
-                                            bool wide, bool wt, const f32x4* held = nullptr) {
+                                            bool wide, bool wt, const f32x4* held = nullptr, NormFold* fold = nullptr) {
   constexpr int ES = (int)sizeof(T);
   static_assert(NB * 32 * ES <= 128, "a chunk row holds 128 bytes");
   static_assert(!ACCUM || ES == 4, "accumulation is for fp32 outputs");
@@ -116,8 +126,19 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
     T* dst = out + row * ld + n;
     if constexpr (ES == 4) {
       f32x4* d4 = reinterpret_cast<f32x4*>(dst);
-      if constexpr (ACCUM) store16(d4, (held ? held[it] : *d4) + piece, wt);
-      else store16(d4, piece, wt);
+      if constexpr (ACCUM) {
+        const f32x4 nx = (held ? held[it] : *d4) + piece;
+        store16(d4, nx, wt);
+        if constexpr (NB == 1) {
+          if (fold) {
+            const f32x4 gg = *reinterpret_cast<const f32x4*>(fold->gain_lds + (n - fold->n0));
+            *reinterpret_cast<u32x2*>(fold->xg + row * fold->ld_xg + n) = pack4(nx[0] * gg[0], nx[1] * gg[1], nx[2] * gg[2], nx[3] * gg[3]);
+            fold->ssacc[it] += (nx[0] * nx[0] + nx[1] * nx[1]) + (nx[2] * nx[2] + nx[3] * nx[3]);
+          }
+        }
+      } else {
+        store16(d4, piece, wt);
+      }
     } else {
       if (wide && n + 8 <= col_end) {
         store16(dst, piece, wt);
@@ -370,6 +391,31 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N;
+  // EXTRA_LDS_BYTES behind the stage buffers: the row scales of a folded RMSNorm (consumer: BM floats), or
+  // the gain of the tile's columns and, from float 256 on, the waves' sums of squares [WGN][BM] (producer)
+  float* extra_lds = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
+  // consumer of a folded RMSNorm: thread t < BM gathers the partial sums of squares of row m0 + t while the
+  // last K slice runs, turns them into 1 / rms behind the K loop and leaves it in LDS for every wave
+  constexpr bool CONSUMES_NORM = EPI == EPI_QKV || EPI == EPI_SWIGLU_BF16;
+  static_assert(!CONSUMES_NORM || 64 * NWAVES >= BM, "one thread per tile row gathers its scale");
+  [[maybe_unused]] float ss_part[8];
+  [[maybe_unused]] auto gather_scale = [&] {
+    if (g.ss_in && (int)threadIdx.x < BM) {
+      int m = m0 + (int)threadIdx.x;
+      m = m < M ? m : M - 1;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ss_part[k] = k < g.ss_parts ? g.ss_in[(int64_t)k * g.ss_stride + m] : 0.f;
+    }
+  };
+  [[maybe_unused]] auto publish_scale = [&] {
+    if (g.ss_in) {
+      if ((int)threadIdx.x < BM) {
+        const float ss = ((ss_part[0] + ss_part[1]) + (ss_part[2] + ss_part[3])) + ((ss_part[4] + ss_part[5]) + (ss_part[6] + ss_part[7]));
+        extra_lds[threadIdx.x] = rsqrtf(ss / (float)g.norm_dim + g.norm_eps);
+      }
+      __syncthreads();
+    }
+  };
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
@@ -390,7 +436,9 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             const int n = n0 + wn * WN + j * 32 + blk_row<MFMA16>(q, lane);
             bv[j][q] = (g.bias && n < N) ? g.bias[n] : 0.f;
           }
+        gather_scale();
       });
+      publish_scale();
       const bool wide = (g.ld_vt & 7) == 0;
       const bool wt_v = lines_exclusive(g.vt, g.ld_vt * 2);   // a workgroup writes 512-byte runs of a v^T row
 #pragma unroll
@@ -403,8 +451,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const int vsub = MFMA16 ? (((q & 1) << 1) | (q >> 1)) : q;
+              // the group's four values are four consecutive tokens: their row scales
+              f32x4 rs = {1.f, 1.f, 1.f, 1.f};
+              if (g.ss_in) rs = *reinterpret_cast<const f32x4*>(extra_lds + wm * WM + (i + ii) * 32 + blk_col<MFMA16>(q, lane));
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * vsub + e] + bv[j][q];
+              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * vsub + e] * rs[e] + bv[j][q];
             }
           store_block<2, bf16_t, false, MFMA16>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
                                         N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide, wt_v);
@@ -468,7 +519,24 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 #pragma unroll
       for (int j = 0; j < TN; ++j) fetch_old(0, j, held[0][j]);
     }
+    if constexpr (CONSUMES_NORM) gather_scale();
   });
+  if constexpr (CONSUMES_NORM) publish_scale();
+  // producer of a folded RMSNorm: the gain of the tile's columns goes to LDS, from where the epilogue's
+  // row-segment lanes read it
+  constexpr bool FOLDS_NORM = EPI == EPI_RESADD_F32;
+  static_assert(!FOLDS_NORM || (BN <= 256 && 1024 + WGN * BM * 4 <= EXTRA_LDS_BYTES), "extra LDS layout");
+  [[maybe_unused]] const bool folding = FOLDS_NORM && g.ss_out != nullptr;
+  if constexpr (FOLDS_NORM) {
+    if (folding) {
+      for (int c = threadIdx.x * 4; c < BN; c += 64 * NWAVES * 4) {
+        int n = n0 + c;
+        n = n < N ? n : N - 4;
+        *reinterpret_cast<f32x4*>(extra_lds + c) = *reinterpret_cast<const f32x4*>(g.norm_gain + n);
+      }
+      __syncthreads();
+    }
+  }
 
   // QKV: the (cos, sin) rows of this tile's BM tokens are staged in LDS (free after the K loop)
   // with coalesced 16-byte loads; read per lane from global they are 16-byte pieces of 32 different
@@ -524,6 +592,16 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   for (int i = 0; i < TM; ++i) {
     const int mrow = m0 + wm * WM + i * 32;  // first row of the block
     if (mrow >= M) continue;                 // wave-uniform
+    // folded RMSNorm, consumer side: 1 / rms of the row each group q of this block holds
+    [[maybe_unused]] float rsq[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (CONSUMES_NORM) {
+      if (g.ss_in) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rsq[q] = extra_lds[mrow - m0 + blk_row<MFMA16>(q, lane)];
+      }
+    }
+    // ... producer side: sums of squares of the updated rows, gathered by the residual store
+    [[maybe_unused]] NormFold fold = {g.xg, g.ld_xg, extra_lds, n0, {0.f, 0.f, 0.f, 0.f}};
     if constexpr (EPI == EPI_SWIGLU_BF16) {
       // output column p*32 + c of the wave pairs gate column 2p*32 + c with up column (2p+1)*32 + c
       auto emit = [&](auto tag, int p0) {
@@ -536,7 +614,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             const int j = 2 * (p0 + b);
             const f32x4 bg = bias_r[j][q % CQ], bu = bias_r[j + 1][q % CQ];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[b][q][e] = silu_f(acc[i][j][4 * q + e] + bg[e]) * (acc[i][j + 1][4 * q + e] + bu[e]);
+            for (int e = 0; e < 4; ++e)
+              v[b][q][e] = silu_f(acc[i][j][4 * q + e] * rsq[q] + bg[e]) * (acc[i][j + 1][4 * q + e] * rsq[q] + bu[e]);
           }
         store_block<NB, bf16_t, false, MFMA16>(chunk, v, static_cast<bf16_t*>(g.out), g.ldo, g.row_map, mrow, M,
                                        (nw >> 1) + p0 * 32, N >> 1, wide, wt);
@@ -559,6 +638,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             f32x4 t;
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
+            if constexpr (EPI == EPI_QKV) t *= rsq[q];
             t += bias_r[j][q % CQ];
             if constexpr (EPI == EPI_RESADD_SCALED_F32) t *= scale_r[j][q % CQ];
             if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
@@ -580,7 +660,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
           store_block<NB, float, true, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
-                                       wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr);
+                                       wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr,
+                                       folding ? &fold : nullptr);
           if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
           }
@@ -613,6 +694,33 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
       } else {
 #pragma unroll
         for (int j0 = 0; j0 < TN; ++j0) emit(int_tag<1>{}, j0);
+      }
+      if constexpr (FOLDS_NORM) {
+        if (folding) {
+          // eight lanes share a row of a 32-column fp32 block: their sums over the wave's columns, added
+          // in a fixed order, are the tile's contribution to the row's sum of squares
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            float s = fold.ssacc[it];
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            s += __shfl_xor(s, 4);
+            if ((lane & 7) == 0) extra_lds[256 + wn * BM + wm * WM + i * 32 + it * 8 + (lane >> 3)] = s;
+          }
+        }
+      }
+    }
+  }
+  if constexpr (FOLDS_NORM) {
+    if (folding) {
+      // the waves' sums over their columns, added in wave order: the tile's share of each row's sum of squares
+      __syncthreads();
+      const int t = threadIdx.x;
+      if (t < BM && m0 + t < M) {
+        float s = extra_lds[256 + t];
+#pragma unroll
+        for (int w2 = 1; w2 < WGN; ++w2) s += extra_lds[256 + w2 * BM + t];
+        g.ss_out[(int64_t)(n0 / BN) * g.ss_stride + m0 + t] = s;
       }
     }
   }
@@ -708,7 +816,8 @@ static bool tail_split_off() {
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = 2 * (BM + BN) * 128;
+  constexpr int LDS = 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES;
+  static_assert(LDS <= 160 * 1024, "LDS of a CU");
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
     snprintf(g.describe, 96, "gemm_kernel<%d, %d, %d, %d, %d, %d>%s", BM, BN, WGM, WGN, EPI, TAIL,
@@ -789,6 +898,18 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     if (big >= 160 && big <= 256 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
+}
+
+int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K) {
+  // ask the launcher itself which tile such a residual GEMM runs on: one partial sum per column tile
+  if (M <= 0 || M > 0x7fffffff || N <= 0 || K <= 0 || (N & 3) || (K & 63)) return 0;
+  char name[96] = {0};
+  GemmArgs g = {};
+  g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K; g.lda = K; g.ldo = N; g.describe = name;
+  int bm = 0, bn = 0;
+  if (launch_gemm(EPI_RESADD_F32, g, nullptr) != CS_OK || sscanf(name, "gemm_kernel<%d, %d", &bm, &bn) != 2 || bn <= 0) return 0;
+  const int64_t parts = (N + bn - 1) / bn;
+  return parts <= 8 ? (int32_t)parts : 0;
 }
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g_in, hipStream_t stream) {
