@@ -770,7 +770,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     // workgroups [0, n_main) run the full rounds; the rest each take half of a tile of the last round
     const int n_main = (tiles_m * tiles_n / CHIP_CUS) * CHIP_CUS;
     if ((int)blockIdx.x >= n_main) {
-      const int t = blockIdx.x - n_main;
+      // (the half tiles get the same treatment as the tiles: consecutive workgroups run on different XCDs,
+      // so every XCD takes a contiguous run of half tiles, both halves of a tile among them)
+      int t = blockIdx.x - n_main;
+      {
+        const int n_half = gridDim.x - n_main, xcd = t & 7, idx = t >> 3;
+        const int per = n_half >> 3, rem = n_half & 7;
+        t = xcd * per + (xcd < rem ? xcd : rem) + idx;
+      }
       int m0, n0;
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
       tile_body<BM / 2, BN, WGM, WGN, EPI>(g, smem, m0 + (t & 1) * (BM / 2), n0);
