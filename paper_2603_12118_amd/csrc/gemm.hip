@@ -160,9 +160,6 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
 #ifndef CS_GEMM_RESADD_WT     // 1: the residual-add epilogue stores write-through like the others
 #define CS_GEMM_RESADD_WT 1
 #endif
-#ifndef CS_GEMM_NARROW8       // the 256 x 160 tile with eight waves of 64 x 80: 0 never, 1 for long K loops, 2 always
-#define CS_GEMM_NARROW8 0
-#endif
 #ifndef CS_GEMM_A_AUX
 #define CS_GEMM_A_AUX 0
 #endif
@@ -372,11 +369,14 @@ struct int_tag { static constexpr int value = V; };
 // 32-column blocks of it (and the epilogue has no pairing of column blocks).
 template <int BN, int WGM, int WGN, int EPI>
 constexpr bool light_tail() {
-  return EPI != EPI_SWIGLU_BF16 && (BN / (WGM * WGN)) % 32 == 0 && (BN / (WGM * WGN)) >= 32;
+  constexpr int WN = BN / (WGM * WGN);                           // columns per wave of the 64-row tile
+  constexpr int UNIT = use_mfma16<WGM * WGN>() ? 16 : 32;          // (a 16x16x32 wave may own half a 32-column block)
+  return EPI != EPI_SWIGLU_BF16 && WN % UNIT == 0 && WN >= UNIT && (EPI != EPI_QKV || WN % 32 == 0);
 }
 
 // One output tile: K loop and epilogue.
-template <int BM, int BN, int WGM, int WGN, int EPI>
+// LDS_ALLOC: bytes of LDS the launch has (that of its largest tile shape).
+template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
@@ -386,7 +386,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   static_assert((EPI != EPI_SWIGLU_BF16 && EPI != EPI_QKV) || WN % 32 == 0, "these epilogues work on whole 32-column blocks");
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
   static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
-  static_assert(NWAVES * CHUNK_BYTES <= STAGE_BYTES, "the epilogue chunks live in the idle stage buffer");
+  // the epilogue chunks live in the idle stage buffer; where that is too small for them (a 64-row tail tile of a
+  // narrow launch) they go behind everything else this tile uses, inside what the launch's main tile shape allocated
+  constexpr bool CHUNKS_BEHIND = NWAVES * CHUNK_BYTES > STAGE_BYTES;
+  static_assert(!CHUNKS_BEHIND || (2 * STAGE_BYTES + EXTRA_LDS_BYTES + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
+                "no room for the epilogue chunks");
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -419,7 +423,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
-  unsigned char* chunk = smem + ((g.K >> 6) & 1) * STAGE_BYTES + wave * CHUNK_BYTES;
+  unsigned char* chunk = CHUNKS_BEHIND ? smem + 2 * STAGE_BYTES + EXTRA_LDS_BYTES + wave * CHUNK_BYTES
+                                       : smem + ((g.K >> 6) & 1) * STAGE_BYTES + wave * CHUNK_BYTES;
 
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= 2 * g.hidden) {
@@ -780,7 +785,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       }
       int m0, n0;
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
-      tile_body<BM / 2, BN, WGM, WGN, EPI>(g, smem, m0 + (t & 1) * (BM / 2), n0);
+      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, m0 + (t & 1) * (BM / 2), n0);
       return;
     }
     nb = n_main;
@@ -790,7 +795,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -863,6 +868,18 @@ static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
   return launch_one<BM, BN, WGM, WGN, EPI, TAIL_NONE>(g, stream);
 }
 
+// Measurement switch: CS_GEMM_NARROW8 in the environment (read once) says when the 256 x 160 tile runs with
+// eight waves of 64 x 80 instead of four of 64 x 160 (and the 256 x 128 tile with eight of 64 x 64 instead of four
+// of 64 x 128): 0 never, 1 for long K loops, 2 (default) always.  Measured on the 8-image step: 11.92 / 11.88 /
+// 11.84 ms for 0 / 1 / 2.
+static int narrow8_mode() {
+  static const int mode = [] {
+    const char* v = getenv("CS_GEMM_NARROW8");
+    return v && *v >= '0' && *v <= '2' ? *v - '0' : 2;
+  }();
+  return mode;
+}
+
 template <int EPI>
 static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // Tile choice by the number of workgroups it yields for the 256 CUs.
@@ -886,18 +903,23 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     // workgroups, one round of the chip at M = 8192
     if constexpr (EIGHT_WAVES_OK) {
       if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) {
-#if CS_GEMM_NARROW8 && CS_GEMM_MFMA16
+#if CS_GEMM_MFMA16
         // eight waves of 64 x 80 (16x16x32 MFMAs, the wave's third 32-column block half used) where the K
         // loop is long: their main loop is 8 % faster, but with two waves per SIMD the residual epilogue can
         // prefetch only one row block of x at a time, which costs more than that at K = 1280 (measured:
         // K = 3456 74 -> 71 us, K = 1280 36.4 -> 37.5 us)
-        if (CS_GEMM_NARROW8 == 2 || g.K >= 2560) return launch_cfg<256, 160, 4, 2, EPI>(g, stream);
+        if (narrow8_mode() == 2 || (narrow8_mode() == 1 && g.K >= 2560)) return launch_cfg<256, 160, 4, 2, EPI>(g, stream);
 #endif
         return launch_cfg<256, 160, 4, 1, EPI>(g, stream);
       }
     }
-    // the same for N = 1024: 256 x 128 tiles
-    if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
+    // the same for N = 1024: 256 x 128 tiles (eight waves of 64 x 64 leave room for the scaled residual epilogue too)
+    if (g.N % 128 == 0 && tm * (g.N / 128) >= 192) {
+#if CS_GEMM_MFMA16
+      if (narrow8_mode() == 2 || (narrow8_mode() == 1 && g.K >= 2560)) return launch_cfg<256, 128, 4, 2, EPI>(g, stream);
+#endif
+      return launch_cfg<256, 128, 4, 1, EPI>(g, stream);
+    }
   }
   if constexpr (EIGHT_WAVES_OK) {
     // 256 x 256 also when it fills one round to 5/8 or more (batches of 2 - 4 images: 2 - 7 % faster than
