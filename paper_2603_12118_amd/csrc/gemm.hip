@@ -880,6 +880,14 @@ static int narrow8_mode() {
   return mode;
 }
 
+static bool narrow_resadd() {
+  static const bool on = [] {
+    const char* v = getenv("CS_GEMM_NARROW_RESADD");
+    return v && *v && *v != '0';
+  }();
+  return on;
+}
+
 template <int EPI>
 static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   // Tile choice by the number of workgroups it yields for the 256 CUs.
@@ -895,8 +903,10 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   }
 #endif
   if constexpr (EIGHT_WAVES_OK) {
-    // 256 x 256 for a round and a half of the chip or more
-    if (big >= 384 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+    // 256 x 256 for a round and a half of the chip or more (CS_GEMM_NARROW_RESADD=1 in the environment makes the
+    // residual add take the narrow tile below at any size, for measurement: the 32-image batch 166.5 -> 177.4 ms)
+    const bool narrow_first = EPI == EPI_RESADD_F32 && g.N % 160 == 0 && narrow_resadd();
+    if (big >= 384 && big_ok && !narrow_first) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
