@@ -736,7 +736,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 //    remaining rows in 64-row tiles (same threads, every wave a 64 x BN/waves strip): they stream the
 //    same W slices but do a quarter of the MFMAs, so that tile row costs microseconds instead of a round
 //    of the chip.
-//  TAIL_SPLIT (M a multiple of BM, the last round of the chip at most half full): the tiles of that
+//  TAIL_SPLIT (no light tail, the last round of the chip at most half full): the tiles of that
 //    last round are cut in two along M and run as BM/2-row tiles by twice as many workgroups, so the
 //    round takes little more than half as long.  A round costs the same however few of its tiles are
 //    there (measured: 864 tiles of 256 x 256 take as long as 1024), and 8192 x 6912 is 3 3/8 rounds.
@@ -785,7 +785,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       }
       int m0, n0;
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
-      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, m0 + (t & 1) * (BM / 2), n0);
+      m0 += (t & 1) * (BM / 2);
+      if (m0 >= M) return;   // the lower half of a tile of a ragged last tile row may be empty
+      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, m0, n0);
       return;
     }
     nb = n_main;
@@ -861,8 +863,8 @@ static cs_status launch_cfg(const GemmArgs& g, hipStream_t stream) {
   }
   // half tiles for a last round that is at most half full (the big tile only: that is where a round is long)
   if constexpr (BM == 256 && BN == 256) {
-    const int tiles = (g.M / BM) * ((g.N + BN - 1) / BN), tail = tiles % CHIP_CUS;
-    if (g.M % BM == 0 && g.splits <= 1 && tiles > CHIP_CUS && tail > 0 && tail <= CHIP_CUS / 2 && !tail_split_off())
+    const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN), tail = tiles % CHIP_CUS;
+    if (g.splits <= 1 && tiles > CHIP_CUS && tail > 0 && tail <= CHIP_CUS / 2 && !tail_split_off())
       return launch_one<BM, BN, WGM, WGN, EPI, TAIL_SPLIT>(g, stream);
   }
   return launch_one<BM, BN, WGM, WGN, EPI, TAIL_NONE>(g, stream);

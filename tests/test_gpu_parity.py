@@ -102,7 +102,8 @@ def test_forward_embeddings_workload_spans():
 @pytest.mark.parametrize("M,N,K", [(64, 64, 64), (1, 8, 64), (100, 36, 192), (300, 200, 128), (1000, 520, 1216),
                                    (257, 3840, 1280), (2048, 1280, 3456), (3000, 1280, 256), (3072, 3840, 128),
                                    (3000, 3840, 192), (8224, 1024, 256),
-                                   (4096, 4352, 128)])     # 272 tiles of 256 x 256: the last 16 run as half tiles
+                                   (4096, 4352, 128),      # 272 tiles of 256 x 256: the last 16 run as half tiles
+                                   (16500, 2048, 64)])     # 520 tiles, a ragged last tile row among the 8 split ones
 def test_linear_matches_oracle(M, N, K):
     rng = np.random.default_rng(M + N)
     A = wl.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
