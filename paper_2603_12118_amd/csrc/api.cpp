@@ -420,7 +420,7 @@ struct Workspace {
 };
 
 // Residual GEMMs of small batches (few workgroups, long K loops) are split over K: up to this many parts
-constexpr int MAX_K_PARTS = 4;
+constexpr int MAX_K_PARTS = PENDING_MAX_PARTS;
 constexpr int64_t SPLIT_K_MAX_TOKENS = 2560;
 
 // Parts for x += A W^T with M rows, N columns, K deep on 128 x 128 tiles: as many (at most MAX_K_PARTS)

@@ -164,6 +164,7 @@ cs_status launch_attention(const AttnArgs& a, hipStream_t stream);
 // Split-K partial sums of a residual GEMM that the next normalisation adds to x on its way through:
 // x[r, n] += scale[n] * (sum over s of parts[s*stride + r*dim + n] + bias[n]), written back to x, then
 // normalised.  parts == nullptr: nothing pending.  scale may be nullptr (1).
+constexpr int PENDING_MAX_PARTS = 4;   // a split-K launch of the encoder leaves at most so many partial sums
 struct PendingSum {
   const float* parts = nullptr;
   int32_t n_parts = 0;

@@ -46,11 +46,16 @@ __global__ __launch_bounds__(256) void norm_kernel(float* __restrict__ x, const 
         v[i].x *= ip; v[i].y *= ip; v[i].z *= ip; v[i].w *= ip;
       }
       if (add.parts) {   // pending split-K sums join the residual stream here (pool == 1)
-        float4 a = reinterpret_cast<const float4*>(add.parts + row * dim)[c];
-        for (int s = 1; s < add.n_parts; ++s) {
-          const float4 t = reinterpret_cast<const float4*>(add.parts + s * add.stride + row * dim)[c];
-          a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
-        }
+        // all parts are requested before the first is used (a loop over a run-time count waits for every
+        // load in turn); summed in part order as before
+        float4 part[PENDING_MAX_PARTS];
+#pragma unroll
+        for (int s = 0; s < PENDING_MAX_PARTS; ++s)
+          if (s < add.n_parts) part[s] = reinterpret_cast<const float4*>(add.parts + s * add.stride + row * dim)[c];
+        float4 a = part[0];
+#pragma unroll
+        for (int s = 1; s < PENDING_MAX_PARTS; ++s)
+          if (s < add.n_parts) { a.x += part[s].x; a.y += part[s].y; a.z += part[s].z; a.w += part[s].w; }
         if (add.bias) {
           const float4 t = reinterpret_cast<const float4*>(add.bias)[c];
           a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
@@ -107,9 +112,11 @@ __global__ __launch_bounds__(256) void norm_kernel(float* __restrict__ x, const 
   }
 }
 
-static cs_status norm_check(int64_t rows, int dim) {
+static cs_status norm_check(int64_t rows, int dim, const PendingSum& add = PendingSum()) {
   if (dim <= 0 || (dim & 3) || dim > 64 * 4 * NORM_MAX_V4)
     return fail(CS_ERR_UNSUPPORTED, "norm: dim must be a multiple of 4, at most 2048");
+  if (add.parts && (add.n_parts < 1 || add.n_parts > PENDING_MAX_PARTS || (add.stride & 3)))
+    return fail(CS_ERR_UNSUPPORTED, "norm: pending sums come in 1 to 4 parts, their stride a multiple of 4");
   if (rows > (int64_t)4 * 0x7fffffff) return fail(CS_ERR_UNSUPPORTED, "norm: too many rows");
   return CS_OK;
 }
@@ -117,7 +124,7 @@ static cs_status norm_check(int64_t rows, int dim) {
 cs_status launch_rmsnorm(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim, hipStream_t s,
                          const PendingSum& add) {
   if (rows <= 0) return CS_OK;
-  if (cs_status st = norm_check(rows, dim)) return st;
+  if (cs_status st = norm_check(rows, dim, add)) return st;
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
                      rows, dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2), add);
   CS_HIP(hipGetLastError());
@@ -127,7 +134,7 @@ cs_status launch_rmsnorm(float* x, const float* gain, float eps, bf16_t* y, int6
 cs_status launch_rmsnorm_split(float* x, const float* gain, float eps, bf16_t* y, int64_t rows, int32_t dim,
                                int32_t group, hipStream_t s, const PendingSum& add) {
   if (rows <= 0) return CS_OK;
-  if (cs_status st = norm_check(rows, dim)) return st;
+  if (cs_status st = norm_check(rows, dim, add)) return st;
   if (group < 1 || rows % group) return fail(CS_ERR_INVALID_ARG, "rmsnorm_split: rows must be a multiple of the group");
   hipLaunchKernelGGL(norm_kernel<0>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, nullptr, eps, y,
                      rows, dim, 1, group, lines_exclusive(y, (int64_t)dim * 2), add);
@@ -138,7 +145,7 @@ cs_status launch_rmsnorm_split(float* x, const float* gain, float eps, bf16_t* y
 cs_status launch_layernorm(float* x, const float* gain, const float* bias, float eps, bf16_t* y, int64_t rows,
                            int32_t dim, hipStream_t s, const PendingSum& add) {
   if (rows <= 0) return CS_OK;
-  if (cs_status st = norm_check(rows, dim)) return st;
+  if (cs_status st = norm_check(rows, dim, add)) return st;
   hipLaunchKernelGGL(norm_kernel<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, gain, bias, eps, y, rows,
                      dim, 1, 0, lines_exclusive(y, (int64_t)dim * 2), add);
   CS_HIP(hipGetLastError());
