@@ -363,7 +363,9 @@ cs_status cs_linear_bf16(const void* A, int64_t lda, const void* W, const float*
  *  vt   bf16 [n_heads*head_dim, ld_vt]    v transposed: vt[h*head_dim+d, token]
  *  seg_cu host int32 [n_seg+1] token boundaries, multiples of 4
  *  out  bf16 [N_tok, n_heads*head_dim]
- * head_dim 64 or 80. */
+ * head_dim 64 or 80.  Unlike the hot calls this one allocates and blocks: it builds the work list of the
+ * segments on the host, uploads it with a hipMalloc and a synchronous copy, and synchronises `stream`
+ * before it returns (cs_encode keeps its work lists in the plan and does neither). */
 cs_status cs_attention_varlen(const void* qk, const void* vt, int64_t ld_vt, void* out, const int32_t* seg_cu,
                               int32_t n_seg, int32_t n_heads, int32_t head_dim, void* stream);
 
