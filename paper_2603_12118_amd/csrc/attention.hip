@@ -134,13 +134,18 @@ void attn_kernel(AttnArgs a) {
     if (!SINGLE && !live) continue;
 
     // ---- S^T tiles: s[it][jt] covers keys kv + jt*32 .. +31 (rows) x queries it*32 .. +31 (lanes)
+    // The accumulators start at minus the query's running maximum (a lane's scores all belong to one
+    // query), so the products come out as score - maximum and the common case below needs no subtraction.
+    const bool first = kv == w.kv0;
     f32x16 s[QT][2];
 #pragma unroll
-    for (int it = 0; it < QT; ++it)
+    for (int it = 0; it < QT; ++it) {
+      const float init = first ? 0.f : -mrun[it];
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[it][jt][r] = 0.f;
+        for (int r = 0; r < 16; ++r) s[it][jt][r] = init;
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -164,7 +169,12 @@ void attn_kernel(AttnArgs a) {
           }
         }
     }
-    // ---- online softmax, per query column
+    // ---- online softmax, per query column.  The running maximum is moved only when a tile's largest score
+    // exceeds it by more than MAX_SLACK (in the log2 domain): probabilities are then at most 2^MAX_SLACK
+    // instead of 1, which changes nothing in the quotient (softmax is invariant under a common shift, and
+    // bf16 and fp32 keep their relative precision over that range), and the accumulators are rescaled
+    // only on the first tile and on such a jump instead of on nearly every tile.
+    constexpr float MAX_SLACK = 8.0f;
     bf16x8 pf[QT][4];
 #pragma unroll
     for (int it = 0; it < QT; ++it) {
@@ -173,13 +183,26 @@ void attn_kernel(AttnArgs a) {
       for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[it][jt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // v_exp_f32 directly: arguments are <= 0 and results that would be denormal may flush to 0,
+      mx = fmaxf(mx, __shfl_xor(mx, 32));          // the tile's largest score minus the running maximum
+      // v_exp_f32 directly: arguments are bounded above and results that would be denormal may flush to 0,
       // so the library exp2f's range scaling (four more instructions per score) buys nothing here
-      const float mnew = fmaxf(mrun[it], mx);      // finite: every tile holds at least one valid key
-      const float alpha = __builtin_amdgcn_exp2f(mrun[it] - mnew);
-      const bool moved = __any(mnew != mrun[it]);  // some query of this wave has a new maximum
-      mrun[it] = mnew;
+      const bool jump = first || mx > MAX_SLACK;   // every tile holds at least one valid key: mx is finite
+      if (__any(jump)) {                           // some query of this wave takes a new maximum
+        const float base = first ? 0.f : mrun[it];
+        const float mnew = jump ? mx + base : mrun[it];
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(mrun[it] - mnew);
+        const float shift = mnew - base;           // 0 in the lanes whose query keeps its maximum
+        mrun[it] = mnew;
+        lrun[it] *= alpha;
+#pragma unroll
+        for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[it][jt][r] -= shift;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[it][dt][r] *= alpha;
+      }
       float sum = 0.f;
 #pragma unroll
       for (int jt = 0; jt < 2; ++jt)
@@ -188,21 +211,15 @@ void attn_kernel(AttnArgs a) {
           uint32_t pk[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e] - mnew);
-            const float p1 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e + 1] - mnew);
+            const float p0 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e]);
+            const float p1 = __builtin_amdgcn_exp2f(s[it][jt][8 * u + 2 * e + 1]);
             sum += p0 + p1;
             pk[e] = pack2_a(p0, p1);
           }
           uint4 t = make_uint4(pk[0], pk[1], pk[2], pk[3]);
           pf[it][jt * 2 + u] = *reinterpret_cast<bf16x8*>(&t);
         }
-      lrun[it] = lrun[it] * alpha + sum;
-      if (moved) {                                 // otherwise alpha is exactly 1 in every lane
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[it][dt][r] *= alpha;
-      }
+      lrun[it] += sum;
     }
     // ---- O^T += V^T P^T.  k-slot e of lane-half lhi in step (jt,u) is key jt*32 + 16u + 8*(e/4) + 4*lhi + e%4
 #pragma unroll
