@@ -32,7 +32,7 @@ __device__ __forceinline__ uint32_t pack2_a(float a, float b) {
 // SINGLE: every work item has at most 64 keys (windows of up to 64 tokens): one tile, nothing to
 // prefetch, so the staging registers are dead before the accumulators come alive.
 template <int DH, int NW, int QT, bool SINGLE>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SINGLE ? 3 : 2, SINGLE ? 3 : 2)))
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SINGLE ? 3 : (NW == 8 && DH <= 64 ? 4 : 2), SINGLE ? 3 : (NW == 8 && DH <= 64 ? 4 : 2))))
 void attn_kernel(AttnArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int KS = DH / 16;            // k-steps of the score product

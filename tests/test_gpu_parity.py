@@ -123,14 +123,20 @@ def test_linear_matches_oracle(M, N, K):
     assert np.abs(outb.float().cpu().numpy() - refb).max() <= 2 ** -8 * np.abs(refb).max() + 1e-6
 
 
-@pytest.mark.parametrize("dh,nh,segs", [(80, 2, [64, 16, 32, 4, 60, 64, 12]), (80, 3, [300, 1028, 64, 516]),
-                                        (64, 2, [256, 40]), (64, 1, [1500])])
-def test_attention_matches_oracle(dh, nh, segs):
+# sharp > 1: queries scaled up and keys growing along the sequence, so that the largest score of a query
+# keeps rising from key tile to key tile by more than the kernel lets its running maximum lag behind
+@pytest.mark.parametrize("dh,nh,segs,sharp", [(80, 2, [64, 16, 32, 4, 60, 64, 12], 1.0), (80, 3, [300, 1028, 64, 516], 1.0),
+                                              (64, 2, [256, 40], 1.0), (64, 1, [1500], 1.0),
+                                              (80, 2, [1028, 200, 64], 6.0), (64, 2, [1500, 70], 6.0)])
+def test_attention_matches_oracle(dh, nh, segs, sharp):
     rng = np.random.default_rng(dh + len(segs))
     cu = np.concatenate([[0], np.cumsum(segs)])
     n, D = int(cu[-1]), nh * dh
-    qs = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32) * np.float32(1.4426950408889634 / math.sqrt(dh)))
-    k = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32))
+    qs = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32) * np.float32(sharp * 1.4426950408889634 / math.sqrt(dh)))
+    k = rng.standard_normal((n, D), dtype=np.float32)
+    if sharp > 1.0:
+        k *= (1.0 + np.arange(n, dtype=np.float32) / np.float32(n))[:, None]
+    k = wl.round_to_bf16(k)
     v = wl.round_to_bf16(rng.standard_normal((n, D), dtype=np.float32))
     item = np.repeat(np.arange(len(segs)), segs)
     q = qs.astype(np.float64) * math.sqrt(dh) * math.log(2.0)        # undo the folded scale for the checker
@@ -144,7 +150,7 @@ def test_attention_matches_oracle(dh, nh, segs):
     B.cs_attention_varlen(qk, vt, out, cu, nh, dh)
     torch.cuda.synchronize()
     err = np.abs(out.float().cpu().numpy() - ref).max()
-    print(f"attention dh={dh} segs={segs}: max err {err:.3g}", flush=True)
+    print(f"attention dh={dh} segs={segs} sharp={sharp}: max err {err:.3g}", flush=True)
     assert err <= 2e-2        # probabilities and outputs are rounded to bf16 (2^-9 relative), |v| up to ~4
 
 
