@@ -32,7 +32,7 @@ __device__ __forceinline__ uint32_t pack2_a(float a, float b) {
 // SINGLE: every work item has at most 64 keys (windows of up to 64 tokens): one tile, nothing to
 // prefetch, so the staging registers are dead before the accumulators come alive.
 template <int DH, int NW, int QT, bool SINGLE>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SINGLE ? 3 : (NW == 8 && DH <= 64 ? 4 : 2), SINGLE ? 3 : (NW == 8 && DH <= 64 ? 4 : 2))))
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(SINGLE ? 3 : (NW == 8 ? 4 : 2), SINGLE ? 3 : (NW == 8 ? 4 : 2))))
 void attn_kernel(AttnArgs a) {
   constexpr int NT = 64 * NW;
   constexpr int KS = DH / 16;            // k-steps of the score product
@@ -40,8 +40,13 @@ void attn_kernel(AttnArgs a) {
   constexpr int KSTR = DH * 2 + 16;      // LDS row stride of the K tile, bytes
   constexpr int VSTR = 64 * 2 + 8;       // LDS row stride of the V^T tile, bytes
   constexpr int KCH = DH / 8;            // 16-byte chunks per K row
+  // Head dimension 80, eight waves: the query fragments wait in LDS (each lane's own 16-byte pieces, read
+  // back in lane order: no conflicts) instead of 20 registers, which brings the kernel under 128 registers
+  // and a second workgroup onto the CU.
+  constexpr bool Q_IN_LDS = DH > 64 && NW == 8;
   __shared__ __align__(16) unsigned char k_lds[64 * KSTR];
   __shared__ __align__(16) unsigned char v_lds[DT * 32 * VSTR];
+  __shared__ __align__(16) unsigned char q_lds[Q_IN_LDS ? QT * KS * NT * 16 : 16];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lhi = lane >> 5;
@@ -65,6 +70,12 @@ void attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[it][ks] = *reinterpret_cast<const bf16x8*>(qbase + (int64_t)row * ldq + ks * 16 + lhi * 8);
+  }
+  if constexpr (Q_IN_LDS) {
+#pragma unroll
+    for (int it = 0; it < QT; ++it)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<bf16x8*>(q_lds + ((it * KS + ks) * NT + tid) * 16) = qf[it][ks];
   }
 
   f32x16 o[QT][DT];
@@ -152,8 +163,11 @@ void attn_kernel(AttnArgs a) {
       for (int jt = 0; jt < 2; ++jt) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(k_lds + (jt * 32 + l31) * KSTR + ks * 32 + lhi * 16);
 #pragma unroll
-        for (int it = 0; it < QT; ++it)
-          s[it][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[it][ks], s[it][jt], 0, 0, 0);
+        for (int it = 0; it < QT; ++it) {
+          bf16x8 q = qf[it][ks];
+          if constexpr (Q_IN_LDS) q = *reinterpret_cast<const bf16x8*>(q_lds + ((it * KS + ks) * NT + tid) * 16);
+          s[it][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q, s[it][jt], 0, 0, 0);
+        }
       }
     }
     // register r of a tile holds key row 8*(r/4) + 4*lhi + r%4
