@@ -315,7 +315,9 @@ cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, cons
  * processes, so their difference is the time the hand-off added after the producer's last kernel).
  * One producer process (any number of its threads and streams) and one consumer thread per channel.
  * create allocates (one hipMalloc, one shared segment) and open maps; the other calls allocate nothing.
- * The creator closes last: cs_xchannel_close of the creator frees the pool and removes the segment. */
+ * The creator closes last: cs_xchannel_close of the creator frees the pool and removes the segment.
+ * close waits for the device first (hipDeviceSynchronize), so that no host function of the closing
+ * process that is still queued behind a publish or a forward refers to the channel afterwards. */
 typedef struct cs_xchannel cs_xchannel;
 typedef enum { CS_XSLOT_FREE = 0, CS_XSLOT_WRITING = 1, CS_XSLOT_PUBLISHING = 2, CS_XSLOT_READY = 3,
                CS_XSLOT_DRAINING = 4 } cs_xslot_state;

@@ -55,7 +55,7 @@ static cs_status slot_of(cs_channel* ch, int32_t slot, const char* who, Slot** o
 
 extern "C" {
 
-cs_status cs_channel_create(int32_t n_slots, size_t slot_bytes, cs_channel** out) {
+cs_status cs_channel_create(int32_t n_slots, size_t slot_bytes, cs_channel** out) try {
   if (!out) return fail(CS_ERR_INVALID_ARG, "cs_channel_create: NULL out");
   *out = nullptr;
   if (n_slots <= 0 || n_slots > CS_CHANNEL_MAX_SLOTS) return fail(CS_ERR_INVALID_ARG, "cs_channel_create: n_slots out of range");
@@ -76,11 +76,11 @@ cs_status cs_channel_create(int32_t n_slots, size_t slot_bytes, cs_channel** out
   }
   *out = ch;
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_channel_create")
 
 void cs_channel_destroy(cs_channel* ch) { free_channel(ch); }
 
-cs_status cs_channel_acquire(cs_channel* ch, size_t bytes, void* producer_stream, int32_t* slot, void** dev_ptr) {
+cs_status cs_channel_acquire(cs_channel* ch, size_t bytes, void* producer_stream, int32_t* slot, void** dev_ptr) try {
   if (!ch || !slot || !dev_ptr) return fail(CS_ERR_INVALID_ARG, "cs_channel_acquire: NULL argument");
   *slot = -1;
   *dev_ptr = nullptr;
@@ -101,9 +101,9 @@ cs_status cs_channel_acquire(cs_channel* ch, size_t bytes, void* producer_stream
     return CS_OK;
   }
   return fail(CS_ERR_BUSY, "cs_channel_acquire: every slot is in use");
-}
+} CS_CATCH_ALL("cs_channel_acquire")
 
-cs_status cs_channel_publish(cs_channel* ch, int32_t slot, int64_t n_rows, int32_t hidden, int32_t dtype, void* producer_stream) {
+cs_status cs_channel_publish(cs_channel* ch, int32_t slot, int64_t n_rows, int32_t hidden, int32_t dtype, void* producer_stream) try {
   Slot* s = nullptr;
   if (cs_status st = slot_of(ch, slot, "cs_channel_publish", &s)) return st;
   if (dtype != CS_F32 && dtype != CS_BF16) return fail(CS_ERR_INVALID_ARG, "cs_channel_publish: dtype");
@@ -119,9 +119,9 @@ cs_status cs_channel_publish(cs_channel* ch, int32_t slot, int64_t n_rows, int32
   s->dtype = dtype;
   s->state = CS_SLOT_READY;
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_channel_publish")
 
-cs_status cs_channel_release(cs_channel* ch, int32_t slot, void* stream) {
+cs_status cs_channel_release(cs_channel* ch, int32_t slot, void* stream) try {
   Slot* s = nullptr;
   if (cs_status st = slot_of(ch, slot, "cs_channel_release", &s)) return st;
   std::lock_guard<std::mutex> lock(ch->mu);
@@ -130,10 +130,10 @@ cs_status cs_channel_release(cs_channel* ch, int32_t slot, void* stream) {
   s->drained_pending = true;
   s->state = CS_SLOT_FREE;
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_channel_release")
 
 cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, const void** dev_ptr, int64_t* n_rows,
-                              int32_t* hidden, int32_t* dtype, int32_t* arrived) {
+                              int32_t* hidden, int32_t* dtype, int32_t* arrived) try {
   Slot* s = nullptr;
   if (cs_status st = slot_of(ch, slot, "cs_channel_describe", &s)) return st;
   std::lock_guard<std::mutex> lock(ch->mu);
@@ -152,10 +152,10 @@ cs_status cs_channel_describe(cs_channel* ch, int32_t slot, int32_t* state, cons
     }
   }
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_channel_describe")
 
 cs_status cs_channel_forward(cs_channel* ch, int32_t slot, const int64_t* placeholder_index, void* dst_seq,
-                             int64_t dst_rows, int32_t* err_flag, void* consumer_stream) {
+                             int64_t dst_rows, int32_t* err_flag, void* consumer_stream) try {
   Slot* s = nullptr;
   if (cs_status st = slot_of(ch, slot, "cs_channel_forward", &s)) return st;
   std::lock_guard<std::mutex> lock(ch->mu);
@@ -178,6 +178,6 @@ cs_status cs_channel_forward(cs_channel* ch, int32_t slot, const int64_t* placeh
   }
   s->state = CS_SLOT_FREE;
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_channel_forward")
 
 }  // extern "C"

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <exception>
+#include <new>
 #include <string>
 
 #include "../../include/cornenc.h"
@@ -14,6 +16,20 @@ typedef uint16_t bf16_t;  // raw bf16 storage word
 // ---- error plumbing -------------------------------------------------------------------
 void set_error(const std::string& msg);
 cs_status fail(cs_status s, const std::string& msg);
+
+// No exception may cross the C boundary (host allocations can throw): the tail of a function-try-block
+// around the body of an extern "C" function that returns a status.
+inline cs_status fail_noexcept(cs_status s, const char* msg) noexcept {
+  try {
+    return fail(s, msg);
+  } catch (...) {
+    return s;
+  }
+}
+#define CS_CATCH_ALL(who)                                                                                        \
+  catch (const std::bad_alloc&) { return ::cs::fail_noexcept(CS_ERR_NO_MEMORY, who ": out of host memory"); }    \
+  catch (const std::exception& ex) { return ::cs::fail_noexcept(CS_ERR_INVALID_ARG, ex.what()); }                \
+  catch (...) { return ::cs::fail_noexcept(CS_ERR_INVALID_ARG, who ": unexpected exception"); }
 
 #define CS_HIP(expr)                                                                          \
   do {                                                                                        \

@@ -179,9 +179,7 @@ cs_status cs_xchannel_create(const char* name, int32_t n_slots, size_t slot_byte
   c->magic = XCH_MAGIC;      // last: an opener that sees it sees everything above
   *out = x;
   return CS_OK;
-} catch (const std::bad_alloc&) {
-  return fail(CS_ERR_NO_MEMORY, "cs_xchannel_create: out of host memory");
-}
+} CS_CATCH_ALL("cs_xchannel_create")
 
 cs_status cs_xchannel_open(const char* name, cs_xchannel** out) try {
   if (!out) return fail(CS_ERR_INVALID_ARG, "cs_xchannel_open: NULL out");
@@ -214,16 +212,17 @@ cs_status cs_xchannel_open(const char* name, cs_xchannel** out) try {
   x->ctl->attached.fetch_add(1);
   *out = x;
   return CS_OK;
-} catch (const std::bad_alloc&) {
-  return fail(CS_ERR_NO_MEMORY, "cs_xchannel_open: out of host memory");
-}
+} CS_CATCH_ALL("cs_xchannel_open")
 
 void cs_xchannel_close(cs_xchannel* x) {
-  if (x && x->ctl && !x->owner) x->ctl->attached.fetch_sub(1);
+  if (!x) return;
+  // host functions of this process that are still queued on a stream refer to this object
+  (void)hipDeviceSynchronize();
+  if (x->ctl && !x->owner) x->ctl->attached.fetch_sub(1);
   xch_free(x);
 }
 
-cs_status cs_xchannel_acquire(cs_xchannel* x, size_t bytes, int32_t* slot, void** dev_ptr) {
+cs_status cs_xchannel_acquire(cs_xchannel* x, size_t bytes, int32_t* slot, void** dev_ptr) try {
   if (!x || !slot || !dev_ptr) return fail(CS_ERR_INVALID_ARG, "cs_xchannel_acquire: NULL argument");
   *slot = -1;
   *dev_ptr = nullptr;
@@ -240,10 +239,10 @@ cs_status cs_xchannel_acquire(cs_xchannel* x, size_t bytes, int32_t* slot, void*
     }
   }
   return fail(CS_ERR_BUSY, "cs_xchannel_acquire: every slot is in use");
-}
+} CS_CATCH_ALL("cs_xchannel_acquire")
 
 cs_status cs_xchannel_publish(cs_xchannel* x, int32_t slot, int64_t n_rows, int32_t hidden, int32_t dtype,
-                              void* producer_stream) {
+                              void* producer_stream) try {
   XSlot* s = nullptr;
   if (cs_status st = xslot(x, slot, "cs_xchannel_publish", &s)) return st;
   if (dtype != CS_F32 && dtype != CS_BF16) return fail(CS_ERR_INVALID_ARG, "cs_xchannel_publish: dtype");
@@ -263,10 +262,10 @@ cs_status cs_xchannel_publish(cs_xchannel* x, int32_t slot, int64_t n_rows, int3
     return fail(CS_ERR_HIP, std::string("cs_xchannel_publish: hipLaunchHostFunc: ") + hipGetErrorString(he));
   }
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_xchannel_publish")
 
 cs_status cs_xchannel_wait(cs_xchannel* x, int64_t timeout_us, int32_t* slot, int64_t* n_rows, int32_t* hidden,
-                           int32_t* dtype) {
+                           int32_t* dtype) try {
   if (!x || !slot) return fail(CS_ERR_INVALID_ARG, "cs_xchannel_wait: NULL argument");
   *slot = -1;
   XCtl* c = x->ctl;
@@ -290,10 +289,10 @@ cs_status cs_xchannel_wait(cs_xchannel* x, int64_t timeout_us, int32_t* slot, in
       nanosleep(&ts, nullptr);
     }
   }
-}
+} CS_CATCH_ALL("cs_xchannel_wait")
 
 cs_status cs_xchannel_forward(cs_xchannel* x, int32_t slot, const int64_t* placeholder_index, void* dst_seq,
-                              int64_t dst_rows, int32_t* err_flag, void* consumer_stream) {
+                              int64_t dst_rows, int32_t* err_flag, void* consumer_stream) try {
   XSlot* s = nullptr;
   if (cs_status st = xslot(x, slot, "cs_xchannel_forward", &s)) return st;
   if (dst_rows < 0) return fail(CS_ERR_INVALID_ARG, "cs_xchannel_forward: negative size");
@@ -324,19 +323,19 @@ cs_status cs_xchannel_forward(cs_xchannel* x, int32_t slot, const int64_t* place
     return fail(CS_ERR_HIP, std::string("cs_xchannel_forward: hipLaunchHostFunc: ") + hipGetErrorString(he));
   }
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_xchannel_forward")
 
-cs_status cs_xchannel_release(cs_xchannel* x, int32_t slot) {
+cs_status cs_xchannel_release(cs_xchannel* x, int32_t slot) try {
   XSlot* s = nullptr;
   if (cs_status st = xslot(x, slot, "cs_xchannel_release", &s)) return st;
   int32_t want = CS_XSLOT_WRITING;
   if (!s->state.compare_exchange_strong(want, CS_XSLOT_FREE, std::memory_order_acq_rel))
     return fail(CS_ERR_INVALID_ARG, "cs_xchannel_release: only a slot that was acquired and not yet published can be released");
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_xchannel_release")
 
 cs_status cs_xchannel_describe(cs_xchannel* x, int32_t slot, int32_t* state, const void** dev_ptr, int64_t* n_rows,
-                               int32_t* hidden, int32_t* dtype, int64_t* t_ready_ns, int64_t* t_placed_ns) {
+                               int32_t* hidden, int32_t* dtype, int64_t* t_ready_ns, int64_t* t_placed_ns) try {
   XSlot* s = nullptr;
   if (cs_status st = xslot(x, slot, "cs_xchannel_describe", &s)) return st;
   const int32_t stt = s->state.load(std::memory_order_acquire);
@@ -349,6 +348,6 @@ cs_status cs_xchannel_describe(cs_xchannel* x, int32_t slot, int32_t* state, con
   if (t_ready_ns) *t_ready_ns = s->t_ready_ns.load(std::memory_order_relaxed);
   if (t_placed_ns) *t_placed_ns = s->t_placed_ns.load(std::memory_order_relaxed);
   return CS_OK;
-}
+} CS_CATCH_ALL("cs_xchannel_describe")
 
 }  // extern "C"
