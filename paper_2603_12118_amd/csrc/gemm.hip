@@ -45,8 +45,10 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 // The 16x16x32 shape is used by the eight-wave tiles (two waves per SIMD).  With one wave per SIMD (the
 // four-wave tiles) it is slower: every other instruction of the wave delays an MFMA of 16 clocks more
 // than one of 32 (measured: down projection 67 -> 106 us).
-template <int NWAVES>
-constexpr bool use_mfma16() { return CS_GEMM_MFMA16 != 0 && NWAVES >= 8; }
+// (The four-wave 128 x 160 tile is launched only where two of its workgroups share a CU, which again makes two
+// waves per SIMD.)
+template <int NWAVES, int BM = 256, int BN = 256>
+constexpr bool use_mfma16() { return CS_GEMM_MFMA16 != 0 && (NWAVES >= 8 || (BM == 128 && BN == 160)); }
 
 // A wave's accumulators are kept per 32 x 32 block of C^T (or C), 16 registers per lane = 4 groups q of
 // 4 consecutive columns of one row.  Which row and columns a lane's group q holds depends on the MFMA:
@@ -202,7 +204,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
                                         int lhi, int wave, f32x16 (&acc)[BM / WGM / 32][(BN / WGN + 31) / 32]) {
   constexpr int TM = BM / WGM / 32, TN = (BN / WGN + 31) / 32;
   constexpr int NWAVES = WGM * WGN;
-  constexpr bool MFMA16 = use_mfma16<NWAVES>();
+  constexpr bool MFMA16 = use_mfma16<NWAVES, BM, BN>();
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = (BN + 8 * NWAVES - 1) / (8 * NWAVES);
   constexpr int RD_PER = 2;     // LDS reads of the next k-step issued behind each of the first MFMAs
   constexpr int SPREAD_KS = 2;  // k-steps over which the next slice's loads are spread (2 measured best of 1..4)
@@ -308,7 +310,7 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
-  constexpr bool MFMA16 = use_mfma16<NWAVES>();
+  constexpr bool MFMA16 = use_mfma16<NWAVES, BM, BN>();
   constexpr int A_LOADS = BM / (8 * NWAVES), B_LOADS = (BN + 8 * NWAVES - 1) / (8 * NWAVES);
   static_assert(BM % (8 * NWAVES) == 0 && BN % 8 == 0, "tile vs waves");
   static_assert(WM % 32 == 0 && WN % (MFMA16 ? 16 : 32) == 0, "wave tile vs MFMA shape");
@@ -382,7 +384,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
   constexpr int STAGE_BYTES = (BM + BN) * 128;
   constexpr int NWAVES = WGM * WGN;
-  constexpr bool MFMA16 = use_mfma16<NWAVES>();
+  constexpr bool MFMA16 = use_mfma16<NWAVES, BM, BN>();
   static_assert((EPI != EPI_SWIGLU_BF16 && EPI != EPI_QKV) || WN % 32 == 0, "these epilogues work on whole 32-column blocks");
   static_assert(EPI != EPI_SWIGLU_BF16 || (TN % 2 == 0), "gate/up pairs need an even number of column tiles");
   static_assert(EPI != EPI_QKV || (TM % 2 == 0), "v tiles leave through LDS two row blocks at a time");
@@ -477,8 +479,9 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // With eight waves there is room for one row block only: it is fetched before the last K slice,
   // and each chunk's registers are refilled for the next row block as soon as the chunk is stored.
   constexpr bool RESADD = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SCALED_F32;
-  constexpr bool HOLD = RESADD && NWAVES <= 4;
-  constexpr bool HOLD_ROW = RESADD && NWAVES > 4;
+  constexpr bool TWO_PER_SIMD = NWAVES > 4 || (BM == 128 && BN == 160);   // 256 registers per wave, not 512
+  constexpr bool HOLD = RESADD && !TWO_PER_SIMD;
+  constexpr bool HOLD_ROW = RESADD && TWO_PER_SIMD;
   [[maybe_unused]] f32x4 held[HOLD ? TM : 1][(HOLD || HOLD_ROW) ? TN : 1][4];
   [[maybe_unused]] auto fetch_old = [&](int i, int j, f32x4 (&dst)[4]) {
     const int r = lane >> 3, c = (lane & 7) * 4;
@@ -757,7 +760,9 @@ __device__ __forceinline__ void tile_origin(int id, int tiles_m, int tiles_n, in
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * WGM * WGN)
+// (the four-wave 128 x 160 tile must leave room for a second workgroup on the CU: 256 registers, not 512)
+__attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_kernel(GemmArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
   if (gridDim.y > 1) {   // split K (plain fp32 partial sums only): this workgroup's part of A, W and of the output
     g.A += (int64_t)blockIdx.y * g.K;
@@ -835,7 +840,7 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
     snprintf(g.describe, 96, "gemm_kernel<%d, %d, %d, %d, %d, %d>%s", BM, BN, WGM, WGN, EPI, TAIL,
-             use_mfma16<WGM * WGN>() ? " 16x16x32" : " 32x32x16");
+             use_mfma16<WGM * WGN, BM, BN>() ? " 16x16x32" : " 32x32x16");
     return CS_OK;
   }
   // one attribute call per instantiation (two threads that both see `false` repeat a harmless call)
@@ -882,6 +887,17 @@ static int narrow8_mode() {
   return mode;
 }
 
+// CS_GEMM_RESADD_PAIR in the environment (read once): 1 runs the residual GEMMs with N = 1280 on 128 x 160 tiles
+// of four waves, two workgroups per CU (independent of each other: one's barriers and epilogue run under the
+// other's MFMAs), instead of one eight-wave 256 x 160 tile per CU; 0 does not.
+static int resadd_pair_mode() {
+  static const int mode = [] {
+    const char* v = getenv("CS_GEMM_RESADD_PAIR");
+    return v && *v >= '0' && *v <= '1' ? *v - '0' : 0;
+  }();
+  return mode;
+}
+
 static bool narrow_resadd() {
   static const bool on = [] {
     const char* v = getenv("CS_GEMM_NARROW_RESADD");
@@ -916,6 +932,9 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     if constexpr (EIGHT_WAVES_OK) {
       if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) {
 #if CS_GEMM_MFMA16
+        if constexpr (EPI == EPI_RESADD_F32) {
+          if (resadd_pair_mode() == 1) return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
+        }
         // eight waves of 64 x 80 (16x16x32 MFMAs, the wave's third 32-column block half used) where the K
         // loop is long: their main loop is 8 % faster, but with two waves per SIMD the residual epilogue can
         // prefetch only one row block of x at a time, which costs more than that at K = 1280 (measured:
