@@ -66,6 +66,9 @@ struct LayerW {
   size_t wqkv, bqkv, wo, bo, w1, b1, w2, b2;  // w1: gate|up interleaved (vit) or fc1 (audio); w2: down / fc2
   size_t g1, be1, g2, be2;                    // norm gains and (LayerNorm towers) norm biases
   size_t ls1 = 0, ls2 = 0;                    // class-token tower: per-channel scales of the two branches
+  // LayerNorm towers, for a LayerNorm folded into the GEMM behind it: shift vector c and bias d of that GEMM
+  // (fold_vectors below); 0 where there are none
+  size_t cqkv = 0, dqkv = 0, c1 = 0, d1 = 0;
 };
 
 }  // namespace cs
@@ -225,6 +228,27 @@ static size_t pack_matrix(Arena& A, const SrcTensor& t, int64_t rows_pad, int64_
   return off;
 }
 
+// LN(x) W^T + b = rs ((x g) W^T - mu c) + d with c[j] = sum_k g[k] W[j][k] and d[j] = b[j] + sum_k beta[k] W[j][k]:
+// what a GEMM needs to take a LayerNorm's place (the product itself runs on bf16(x g); rs and mu come from
+// per-row sums).  W, b as packed (bf16 rows in the GEMM's order, fp32 bias), g and beta fp32 [K].
+static void fold_vectors(Arena& A, size_t w, size_t bias, size_t gain, size_t beta, int64_t rows, int64_t K, size_t* c_off,
+                         size_t* d_off) {
+  *c_off = A.alloc((size_t)rows * 4);
+  *d_off = A.alloc((size_t)rows * 4);
+  const bf16_t* W = A.bf(w);
+  const float *b = A.f32(bias), *g = A.f32(gain), *be = beta ? A.f32(beta) : nullptr;
+  for (int64_t j = 0; j < rows; ++j) {
+    double c = 0.0, d = b[j];
+    for (int64_t k = 0; k < K; ++k) {
+      const double wv = host_bf2f(W[j * K + k]);
+      c += wv * g[k];
+      if (be) d += wv * be[k];
+    }
+    A.f32(*c_off)[j] = (float)c;
+    A.f32(*d_off)[j] = (float)d;
+  }
+}
+
 template <class RowOf>
 static size_t pack_vector(Arena& A, const SrcTensor& t, int64_t n_pad, RowOf idx_of) {
   const size_t off = A.alloc((size_t)n_pad * 4);
@@ -311,6 +335,8 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
       if (cs_status st = wb.get(p + "mlp.fc2.bias", D, b, true)) return st;
       L.w2 = pack_matrix(A, t, D, I, Ip, ident);
       L.b2 = pack_vector(A, b, D, ident);
+      fold_vectors(A, L.wqkv, L.bqkv, L.g1, L.be1, 3 * D, D, &L.cqkv, &L.dqkv);
+      fold_vectors(A, L.w1, L.b1, L.g2, L.be2, Ip, D, &L.c1, &L.d1);
     }
   }
   if (c.arch == CS_ARCH_VIT || c.arch == CS_ARCH_VIT_CLS) {
@@ -415,6 +441,7 @@ static cs_status build_weights(cs_encoder* e, const WeightBook& wb, Arena& A) {
 struct Workspace {
   size_t plan, rope, x, xn, attn, qk, vt, big, parts, ss, total;
   int64_t ld_vt, ss_stride;
+  size_t s1 = 0;              // LayerNorm towers: per-row partial plain sums, laid out like ss
   int fold_proj, fold_down;   // column tiles of the two residual GEMMs when they fold the next RMSNorm (0: they do not)
   bool split_k;   // small batches: the residual GEMMs run split over K into `parts`
 };
@@ -479,10 +506,12 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   // RMSNorm folded into the GEMMs around it (vision tower, unsplit residual GEMMs): per-row partial sums of
   // squares, one per column tile of the residual GEMM
   w.ss_stride = round_up(N, 64);
-  const bool fold = c.arch == CS_ARCH_VIT && !w.split_k && !fold_off();
-  w.fold_proj = fold ? gemm_norm_fold_parts(N, D, D) : 0;
-  w.fold_down = fold ? gemm_norm_fold_parts(N, D, e->I_pad) : 0;
+  const bool fold = !w.split_k && !fold_off();
+  const bool ln = c.arch != CS_ARCH_VIT, scaled = c.arch == CS_ARCH_VIT_CLS;
+  w.fold_proj = fold ? gemm_norm_fold_parts(N, D, D, scaled, ln) : 0;
+  w.fold_down = fold ? gemm_norm_fold_parts(N, D, e->I_pad, scaled, ln) : 0;
   w.ss = take((w.fold_proj || w.fold_down) ? (size_t)8 * w.ss_stride * 4 : 0);
+  w.s1 = take(ln && (w.fold_proj || w.fold_down) ? (size_t)8 * w.ss_stride * 4 : 0);
   w.total = off;
   return w;
 }
@@ -869,10 +898,15 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
   // xn = bf16(x * gain) and per-row sums of squares, the GEMM behind it scales its rows by 1 / rms.  folded > 0:
   // xn and ss are in that state, with so many partial sums per row.
   float* ss = reinterpret_cast<float*>(ws + w.ss);
+  float* s1 = reinterpret_cast<float*>(ws + w.s1);
   int folded = 0;
-  auto consume_norm = [&](GemmArgs& g) {
+  // shift, bias: the LayerNorm towers' vectors c and d of this GEMM (0 for the RMSNorm tower)
+  auto consume_norm = [&](GemmArgs& g, size_t shift = 0, size_t bias = 0) {
     if (!folded) return;
     g.ss_in = ss; g.ss_parts = folded; g.ss_stride = w.ss_stride; g.norm_dim = (int32_t)D; g.norm_eps = c.norm_eps;
+    if (!vit) {
+      g.s1_in = s1; g.norm_shift = e->ptr<float>(shift); g.bias = e->ptr<float>(bias);
+    }
     folded = 0;
   };
   auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K, size_t next_gain,
@@ -890,8 +924,9 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     }
     g.bias = e->ptr<float>(bias); g.out = x; g.K = (int32_t)K;
     if (scale) g.col_scale = e->ptr<float>(scale);
-    if (!scale && next_gain && fold_parts > 0) {
+    if (next_gain && fold_parts > 0) {
       g.norm_gain = e->ptr<float>(next_gain); g.xg = xn; g.ld_xg = D; g.ss_out = ss; g.ss_stride = w.ss_stride;
+      if (!vit) g.s1_out = s1;
       folded = fold_parts;
     }
     return launch_gemm(scale ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32, g, stream);
@@ -943,7 +978,7 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
       g.out = qk; g.ldo = 2 * D; g.M = (int32_t)N; g.N = (int32_t)(3 * D); g.K = (int32_t)D;
       g.vt = vt; g.ld_vt = w.ld_vt; g.rope_cs = e->rope ? rope_cs : nullptr;
       g.hidden = (int32_t)D; g.head_dim = c.head_dim; g.q_scale = q_scale;
-      consume_norm(g);
+      consume_norm(g, L.cqkv, L.dqkv);
       if (cs_status st = launch_gemm(EPI_QKV, g, stream)) return st;
     }
     const bool full = !vit || c.window <= 0 || ((c.full_attn_layer_mask >> l) & 1);
@@ -962,7 +997,7 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);
-      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D, vit ? L.g2 : 0, w.fold_proj)) return st;
+      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D, L.g2, w.fold_proj)) return st;
     }
     if (cs_status st = norm(L.g2, L.be2)) return st;
     {
@@ -974,12 +1009,18 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
         consume_norm(g);
         if (cs_status st = launch_gemm(EPI_SWIGLU_BF16, g, stream)) return st;
       }
-      else { if (cs_status st = gemm(EPI_GELU_BF16, xn, D, L.w1, L.b1, big, e->I_pad, N, e->I_pad, D, nullptr)) return st; }
+      else {
+        GemmArgs g = {};
+        g.A = xn; g.lda = D; g.W = e->ptr<bf16_t>(L.w1); g.bias = e->ptr<float>(L.b1); g.out = big; g.ldo = e->I_pad;
+        g.M = (int32_t)N; g.N = e->I_pad; g.K = (int32_t)D;
+        consume_norm(g, L.c1, L.d1);
+        if (cs_status st = launch_gemm(EPI_GELU_BF16, g, stream)) return st;
+      }
     }
     {
       StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
       // (the norm behind the last block is the merger's, which splits its output: a kernel of its own)
-      const size_t next_g1 = vit && l + 1 < c.n_layers ? e->layers[l + 1].g1 : 0;
+      const size_t next_g1 = l + 1 < c.n_layers ? e->layers[l + 1].g1 : 0;
       if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad, next_g1, w.fold_down)) return st;
     }
   }

@@ -50,7 +50,9 @@ enum GemmEpilogue {
   EPI_SWIGLU_BF16 = 5,// weight rows interleaved in blocks of 32: gate | up; out[:, j] = silu(g) * u
   EPI_QKV = 6,        // q,k: bias, rotary, (q: scale) -> bf16 row-major; v: bias -> bf16 transposed
   EPI_GELU_SPLIT = 7, // v = gelu(acc + bias) -> bf16 hi at column n and bf16 lo = v - hi at column N + n
-  EPI_RESADD_SCALED_F32 = 8  // out += col_scale * (acc + bias)   (a learned per-channel scale on the branch)
+  EPI_RESADD_SCALED_F32 = 8, // out += col_scale * (acc + bias)   (a learned per-channel scale on the branch)
+  EPI_RESADD_SUMS_F32 = 9    // EPI_RESADD_F32 whose folded normalisation is a LayerNorm (plain sums as well);
+                             // launch_gemm picks it for EPI_RESADD_F32 with s1_out set
 };
 
 struct GemmArgs {
@@ -82,11 +84,22 @@ struct GemmArgs {
   //    x_new[m, n]^2 over the tile's columns;
   //  consumer (EPI_QKV, EPI_SWIGLU_BF16): with ss_in set, row m of A W^T is multiplied by
   //    rsqrt(sum over ss_parts of ss_in[p * ss_stride + m] / norm_dim + norm_eps) before the bias is added.
+  // LayerNorm folds the same way: LN(x) W^T + b = rs ((x g) W^T - mu c) + d with rs = 1/sqrt(var + eps),
+  // c[n] = sum_k g[k] W[n, k] and d[n] = b[n] + sum_k beta[k] W[n, k], both made once from the weights.
+  //  producer (also EPI_RESADD_SCALED_F32): with s1_out set it writes the sums of x_new[m, n] as well,
+  //    laid out like ss_out;
+  //  consumer (EPI_QKV, EPI_GELU_BF16): with s1_in set, mu = sum1 / norm_dim, var = sum2 / norm_dim - mu^2, and
+  //    row m of A W^T becomes rs (A W^T)[m, n] - rs mu norm_shift[n] before the bias (= d) is added.
+  //    (bf16(x g) is not centred: its rounding is relative to |x g|, so this is for rows whose mean is
+  //    small against their deviation, as the rows of a pre-norm residual stream are.)
   const float* norm_gain;
   bf16_t* xg;
   int64_t ld_xg;
   float* ss_out;
+  float* s1_out;
   const float* ss_in;
+  const float* s1_in;
+  const float* norm_shift;
   int32_t ss_parts;
   int64_t ss_stride;
   int32_t norm_dim;
@@ -99,7 +112,7 @@ struct GemmArgs {
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);
 // Column tiles (= partial sums of squares per row) of a residual GEMM that can fold the next RMSNorm into its
 // epilogue for M rows and N columns, or 0 if that launch would not run on the tile that supports it.
-int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K);
+int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K, bool scaled = false, bool sums = false);
 
 // ---- write-through global stores -----------------------------------------------------------
 // Every XCD has its own L2, and the end of a kernel writes back whatever is dirty in it before the

@@ -77,7 +77,13 @@ __device__ __forceinline__ float silu_f(float z) {
 // through a private 32-row LDS chunk and writes them out as whole 64- or 128-byte row segments,
 // 16 bytes per lane.  LDS serves one wave's instructions in order, so no wait is needed between a
 // chunk's writes and reads beyond keeping the compiler from reordering them.
-constexpr int EXTRA_LDS_BYTES = 1024 + 4 * 256 * 4;   // what a tile may use behind its two stage buffers
+// What a tile may use behind its two stage buffers: 1 KB of per-column values, then the waves' per-row partial
+// sums of a folded normalisation, [2][WGN][BM] floats (sums of squares, plain sums).  (The four-wave 128 x 160
+// tile, which must fit a CU twice, keeps room for one of the two and folds RMSNorm only.)
+constexpr int EXTRA_LDS_BYTES = 1024 + 2 * 4 * 256 * 4;
+constexpr int EXTRA_LDS_BYTES_PAIR = 1024 + 4 * 256 * 4;
+template <int BM, int BN>
+constexpr int extra_lds_bytes() { return BM == 128 && BN == 160 ? EXTRA_LDS_BYTES_PAIR : EXTRA_LDS_BYTES; }
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
@@ -91,9 +97,10 @@ struct NormFold {
   const float* gain_lds;  // gain of the tile's columns, staged in LDS; index = column - n0
   int n0;
   float ssacc[4];         // this lane's sums of x_new^2, one per 8-row group of the 32-row block
+  float s1acc[4];         // ... and of x_new (a LayerNorm needs the mean too)
 };
 
-template <int NB, typename T, bool ACCUM, bool MFMA16>
+template <int NB, typename T, bool ACCUM, bool MFMA16, bool SUMS = false>
 __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&v)[NB][4], T* out, int64_t ld,
                                             const int32_t* row_map, int row0, int row_end, int col0, int col_end,
                                             bool wide, bool wt, const f32x4* held = nullptr, NormFold* fold = nullptr) {
@@ -136,6 +143,7 @@ __device__ __forceinline__ void store_block(unsigned char* chunk, const f32x4 (&
             const f32x4 gg = *reinterpret_cast<const f32x4*>(fold->gain_lds + (n - fold->n0));
             *reinterpret_cast<u32x2*>(fold->xg + row * fold->ld_xg + n) = pack4(nx[0] * gg[0], nx[1] * gg[1], nx[2] * gg[2], nx[3] * gg[3]);
             fold->ssacc[it] += (nx[0] * nx[0] + nx[1] * nx[1]) + (nx[2] * nx[2] + nx[3] * nx[3]);
+            if constexpr (SUMS) fold->s1acc[it] += (nx[0] + nx[1]) + (nx[2] + nx[3]);
           }
         }
       } else {
@@ -378,7 +386,7 @@ constexpr bool light_tail() {
 
 // One output tile: K loop and epilogue.
 // LDS_ALLOC: bytes of LDS the launch has (that of its largest tile shape).
-template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>
+template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
@@ -391,41 +399,91 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // the epilogue chunks live in the idle stage buffer; where that is too small for them (a 64-row tail tile of a
   // narrow launch) they go behind everything else this tile uses, inside what the launch's main tile shape allocated
   constexpr bool CHUNKS_BEHIND = NWAVES * CHUNK_BYTES > STAGE_BYTES;
-  static_assert(!CHUNKS_BEHIND || (2 * STAGE_BYTES + EXTRA_LDS_BYTES + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
+  constexpr int XTRA = extra_lds_bytes<BM, BN>();
+  static_assert(!CHUNKS_BEHIND || (2 * STAGE_BYTES + XTRA + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
                 "no room for the epilogue chunks");
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int M = g.M, N = g.N;
-  // EXTRA_LDS_BYTES behind the stage buffers: the row scales of a folded RMSNorm (consumer: BM floats), or
-  // the gain of the tile's columns and, from float 256 on, the waves' sums of squares [WGN][BM] (producer)
+  // The extra LDS behind the stage buffers.  Consumer of a folded normalisation: BM row scales, BM row shifts
+  // (LayerNorm: mean times scale) and BN column values of norm_shift.  Producer: the gain of the tile's columns
+  // and, from float 256 on, the waves' sums of squares [WGN][BM] and plain sums [WGN][BM].
   float* extra_lds = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
-  // consumer of a folded RMSNorm: thread t < BM gathers the partial sums of squares of row m0 + t while the
-  // last K slice runs, turns them into 1 / rms behind the K loop and leaves it in LDS for every wave
-  constexpr bool CONSUMES_NORM = EPI == EPI_QKV || EPI == EPI_SWIGLU_BF16;
+  // consumer: thread t < BM gathers the partial sums of squares of row m0 + t while the last K slice runs
+  // (thread BM + t the partial plain sums, for a LayerNorm), they are turned into 1 / rms (or 1 / sigma and
+  // mean / sigma) behind the K loop and left in LDS for every wave
+  constexpr bool CONSUMES_NORM = EPI == EPI_QKV || EPI == EPI_SWIGLU_BF16 || EPI == EPI_GELU_BF16;
+  constexpr bool CONSUMES_LAYERNORM = EPI == EPI_QKV || EPI == EPI_GELU_BF16;
   static_assert(!CONSUMES_NORM || 64 * NWAVES >= BM, "one thread per tile row gathers its scale");
+  static_assert(!CONSUMES_LAYERNORM || 64 * NWAVES >= 2 * BM || NWAVES <= 4, "a second thread per tile row gathers its sum");
+  static_assert(!CONSUMES_NORM || (2 * BM + BN) * 4 <= XTRA, "extra LDS layout of a consumer");
+  constexpr bool TWO_GATHERERS = 64 * NWAVES >= 2 * BM;
   [[maybe_unused]] float ss_part[8];
+  [[maybe_unused]] float s1_part[(CONSUMES_LAYERNORM && !TWO_GATHERERS) ? 8 : 1];
+  [[maybe_unused]] const bool layer_norm = CONSUMES_LAYERNORM && g.s1_in != nullptr;
   [[maybe_unused]] auto gather_scale = [&] {
-    if (g.ss_in && (int)threadIdx.x < BM) {
-      int m = m0 + (int)threadIdx.x;
+    if (!g.ss_in) return;
+    const int t = (int)threadIdx.x;
+    if (t < BM) {
+      int m = m0 + t;
       m = m < M ? m : M - 1;
 #pragma unroll
       for (int k = 0; k < 8; ++k) ss_part[k] = k < g.ss_parts ? g.ss_in[(int64_t)k * g.ss_stride + m] : 0.f;
+      if constexpr (CONSUMES_LAYERNORM && !TWO_GATHERERS) {
+        if (layer_norm) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) s1_part[k] = k < g.ss_parts ? g.s1_in[(int64_t)k * g.ss_stride + m] : 0.f;
+        }
+      }
+    } else if constexpr (CONSUMES_LAYERNORM && TWO_GATHERERS) {
+      if (layer_norm && t < 2 * BM) {
+        int m = m0 + t - BM;
+        m = m < M ? m : M - 1;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) ss_part[k] = k < g.ss_parts ? g.s1_in[(int64_t)k * g.ss_stride + m] : 0.f;
+      }
     }
   };
   [[maybe_unused]] auto publish_scale = [&] {
-    if (g.ss_in) {
-      if ((int)threadIdx.x < BM) {
-        const float ss = ((ss_part[0] + ss_part[1]) + (ss_part[2] + ss_part[3])) + ((ss_part[4] + ss_part[5]) + (ss_part[6] + ss_part[7]));
-        extra_lds[threadIdx.x] = rsqrtf(ss / (float)g.norm_dim + g.norm_eps);
+    if (!g.ss_in) return;
+    const int t = (int)threadIdx.x;
+    const float tot = ((ss_part[0] + ss_part[1]) + (ss_part[2] + ss_part[3])) + ((ss_part[4] + ss_part[5]) + (ss_part[6] + ss_part[7]));
+    if constexpr (CONSUMES_LAYERNORM) {
+      if (layer_norm) {
+        // the shift vector of the tile's columns, and the rows' statistics
+        for (int c = t * 4; c < BN; c += 64 * NWAVES * 4) {
+          int n = n0 + c;
+          n = n < N ? n : N - 4;
+          *reinterpret_cast<f32x4*>(extra_lds + 2 * BM + c) = *reinterpret_cast<const f32x4*>(g.norm_shift + n);
+        }
+        float sum1;
+        if constexpr (TWO_GATHERERS) {
+          if (t >= BM && t < 2 * BM) extra_lds[t] = tot;   // thread BM + r: the plain sum of row r
+          __syncthreads();
+          sum1 = t < BM ? extra_lds[BM + t] : 0.f;
+        } else {
+          sum1 = ((s1_part[0] + s1_part[1]) + (s1_part[2] + s1_part[3])) + ((s1_part[4] + s1_part[5]) + (s1_part[6] + s1_part[7]));
+        }
+        if (t < BM) {
+          const float inv_d = 1.0f / (float)g.norm_dim;
+          const float mean = sum1 * inv_d;
+          const float var = fmaxf(tot * inv_d - mean * mean, 0.f);
+          const float rs = rsqrtf(var + g.norm_eps);
+          extra_lds[t] = rs;
+          extra_lds[BM + t] = mean * rs;
+        }
+        __syncthreads();
+        return;
       }
-      __syncthreads();
     }
+    if (t < BM) extra_lds[t] = rsqrtf(tot / (float)g.norm_dim + g.norm_eps);
+    __syncthreads();
   };
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
-  unsigned char* chunk = CHUNKS_BEHIND ? smem + 2 * STAGE_BYTES + EXTRA_LDS_BYTES + wave * CHUNK_BYTES
+  unsigned char* chunk = CHUNKS_BEHIND ? smem + 2 * STAGE_BYTES + XTRA + wave * CHUNK_BYTES
                                        : smem + ((g.K >> 6) & 1) * STAGE_BYTES + wave * CHUNK_BYTES;
 
   if constexpr (EPI == EPI_QKV) {
@@ -459,10 +517,15 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             for (int q = 0; q < 4; ++q) {
               const int vsub = MFMA16 ? (((q & 1) << 1) | (q >> 1)) : q;
               // the group's four values are four consecutive tokens: their row scales
-              f32x4 rs = {1.f, 1.f, 1.f, 1.f};
+              f32x4 rs = {1.f, 1.f, 1.f, 1.f}, sh = {0.f, 0.f, 0.f, 0.f};
+              float cn = 0.f;   // LayerNorm: the shift of this v dimension
               if (g.ss_in) rs = *reinterpret_cast<const f32x4*>(extra_lds + wm * WM + (i + ii) * 32 + blk_col<MFMA16>(q, lane));
+              if (layer_norm) {
+                sh = *reinterpret_cast<const f32x4*>(extra_lds + BM + wm * WM + (i + ii) * 32 + blk_col<MFMA16>(q, lane));
+                cn = extra_lds[2 * BM + wn * WN + j * 32 + blk_row<MFMA16>(q, lane)];
+              }
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * vsub + e] * rs[e] + bv[j][q];
+              for (int e = 0; e < 4; ++e) v[ii][q][e] = acc[i + ii][j][4 * vsub + e] * rs[e] - sh[e] * cn + bv[j][q];
             }
           store_block<2, bf16_t, false, MFMA16>(chunk, v, g.vt, g.ld_vt, nullptr, n0 + wn * WN + j * 32 - 2 * g.hidden,
                                         N - 2 * g.hidden, m0 + wm * WM + i * 32, M, wide, wt_v);
@@ -478,7 +541,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
   // With eight waves there is room for one row block only: it is fetched before the last K slice,
   // and each chunk's registers are refilled for the next row block as soon as the chunk is stored.
-  constexpr bool RESADD = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SCALED_F32;
+  constexpr bool RESADD = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SCALED_F32 || EPI == EPI_RESADD_SUMS_F32;
   constexpr bool TWO_PER_SIMD = NWAVES > 4 || (BM == 128 && BN == 160);   // 256 registers per wave, not 512
   constexpr bool HOLD = RESADD && !TWO_PER_SIMD;
   constexpr bool HOLD_ROW = RESADD && TWO_PER_SIMD;
@@ -532,9 +595,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   if constexpr (CONSUMES_NORM) publish_scale();
   // producer of a folded RMSNorm: the gain of the tile's columns goes to LDS, from where the epilogue's
   // row-segment lanes read it
-  constexpr bool FOLDS_NORM = EPI == EPI_RESADD_F32;
-  static_assert(!FOLDS_NORM || (BN <= 256 && 1024 + WGN * BM * 4 <= EXTRA_LDS_BYTES), "extra LDS layout");
+  constexpr bool FOLDS_NORM = RESADD;
+  constexpr bool FOLDS_SUMS = (EPI == EPI_RESADD_SCALED_F32 || EPI == EPI_RESADD_SUMS_F32) && 1024 + 2 * WGN * BM * 4 <= XTRA;
+  static_assert(!FOLDS_NORM || (BN <= 256 && 1024 + WGN * BM * 4 <= XTRA), "extra LDS layout");
   [[maybe_unused]] const bool folding = FOLDS_NORM && g.ss_out != nullptr;
+  [[maybe_unused]] const bool folding_sums = FOLDS_SUMS && folding && g.s1_out != nullptr;
   if constexpr (FOLDS_NORM) {
     if (folding) {
       for (int c = threadIdx.x * 4; c < BN; c += 64 * NWAVES * 4) {
@@ -602,14 +667,21 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
     if (mrow >= M) continue;                 // wave-uniform
     // folded RMSNorm, consumer side: 1 / rms of the row each group q of this block holds
     [[maybe_unused]] float rsq[4] = {1.f, 1.f, 1.f, 1.f};
+    [[maybe_unused]] float msq[CONSUMES_LAYERNORM ? 4 : 1] = {};   // LayerNorm: mean / sigma of those rows
     if constexpr (CONSUMES_NORM) {
       if (g.ss_in) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) rsq[q] = extra_lds[mrow - m0 + blk_row<MFMA16>(q, lane)];
       }
     }
+    if constexpr (CONSUMES_LAYERNORM) {
+      if (layer_norm) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) msq[q] = extra_lds[BM + mrow - m0 + blk_row<MFMA16>(q, lane)];
+      }
+    }
     // ... producer side: sums of squares of the updated rows, gathered by the residual store
-    [[maybe_unused]] NormFold fold = {g.xg, g.ld_xg, extra_lds, n0, {0.f, 0.f, 0.f, 0.f}};
+    [[maybe_unused]] NormFold fold = {g.xg, g.ld_xg, extra_lds, n0, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     if constexpr (EPI == EPI_SWIGLU_BF16) {
       // output column p*32 + c of the wave pairs gate column 2p*32 + c with up column (2p+1)*32 + c
       auto emit = [&](auto tag, int p0) {
@@ -646,7 +718,10 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             f32x4 t;
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = acc[i][j][4 * q + e];
-            if constexpr (EPI == EPI_QKV) t *= rsq[q];
+            if constexpr (CONSUMES_NORM && EPI != EPI_SWIGLU_BF16) t *= rsq[q];
+            if constexpr (CONSUMES_LAYERNORM) {
+              if (layer_norm) t -= msq[q] * *reinterpret_cast<const f32x4*>(extra_lds + 2 * BM + (n - n0));
+            }
             t += bias_r[j][q % CQ];
             if constexpr (EPI == EPI_RESADD_SCALED_F32) t *= scale_r[j][q % CQ];
             if constexpr (EPI == EPI_GELU_BF16 || EPI == EPI_GELU_F32 || EPI == EPI_GELU_SPLIT) {
@@ -667,7 +742,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
           }
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
-          store_block<NB, float, true, MFMA16>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
+          store_block<NB, float, true, MFMA16, FOLDS_SUMS>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
                                        wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr,
                                        folding ? &fold : nullptr);
           if constexpr (HOLD_ROW) {
@@ -715,6 +790,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
             s += __shfl_xor(s, 4);
             if ((lane & 7) == 0) extra_lds[256 + wn * BM + wm * WM + i * 32 + it * 8 + (lane >> 3)] = s;
           }
+          if constexpr (FOLDS_SUMS) {
+            if (folding_sums) {
+#pragma unroll
+              for (int it = 0; it < 4; ++it) {
+                float s = fold.s1acc[it];
+                s += __shfl_xor(s, 1);
+                s += __shfl_xor(s, 2);
+                s += __shfl_xor(s, 4);
+                if ((lane & 7) == 0) extra_lds[256 + (WGN + wn) * BM + wm * WM + i * 32 + it * 8 + (lane >> 3)] = s;
+              }
+            }
+          }
         }
       }
     }
@@ -729,6 +816,14 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 #pragma unroll
         for (int w2 = 1; w2 < WGN; ++w2) s += extra_lds[256 + w2 * BM + t];
         g.ss_out[(int64_t)(n0 / BN) * g.ss_stride + m0 + t] = s;
+        if constexpr (FOLDS_SUMS) {
+          if (folding_sums) {
+            float s1 = extra_lds[256 + WGN * BM + t];
+#pragma unroll
+            for (int w2 = 1; w2 < WGN; ++w2) s1 += extra_lds[256 + (WGN + w2) * BM + t];
+            g.s1_out[(int64_t)(n0 / BN) * g.ss_stride + m0 + t] = s1;
+          }
+        }
       }
     }
   }
@@ -792,7 +887,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
       m0 += (t & 1) * (BM / 2);
       if (m0 >= M) return;   // the lower half of a tile of a ragged last tile row may be empty
-      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, m0, n0);
+      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>(g, smem, m0, n0);
       return;
     }
     nb = n_main;
@@ -802,7 +897,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI, 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI, 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -835,7 +930,7 @@ static bool tail_split_off() {
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = 2 * (BM + BN) * 128 + EXTRA_LDS_BYTES;
+  constexpr int LDS = 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>();
   static_assert(LDS <= 160 * 1024, "LDS of a CU");
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
@@ -933,7 +1028,7 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
       if (g.N % 160 == 0 && tm * (g.N / 160) >= 192) {
 #if CS_GEMM_MFMA16
         if constexpr (EPI == EPI_RESADD_F32) {
-          if (resadd_pair_mode() == 1) return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
+          if (resadd_pair_mode() == 1 && !g.s1_out) return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
         }
         // eight waves of 64 x 80 (16x16x32 MFMAs, the wave's third 32-column block half used) where the K
         // loop is long: their main loop is 8 % faster, but with two waves per SIMD the residual epilogue can
@@ -960,14 +1055,17 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }
 
-int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K) {
+int32_t gemm_norm_fold_parts(int64_t M, int64_t N, int64_t K, bool scaled, bool sums) {
   // ask the launcher itself which tile such a residual GEMM runs on: one partial sum per column tile
   if (M <= 0 || M > 0x7fffffff || N <= 0 || K <= 0 || (N & 3) || (K & 63)) return 0;
   char name[96] = {0};
   GemmArgs g = {};
   g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K; g.lda = K; g.ldo = N; g.describe = name;
+  g.col_scale = scaled ? reinterpret_cast<const float*>(uintptr_t(16)) : nullptr;   // only its alignment is looked at
+  g.s1_out = sums ? reinterpret_cast<float*>(uintptr_t(16)) : nullptr;              // a LayerNorm tower: sums as well
   int bm = 0, bn = 0;
-  if (launch_gemm(EPI_RESADD_F32, g, nullptr) != CS_OK || sscanf(name, "gemm_kernel<%d, %d", &bm, &bn) != 2 || bn <= 0) return 0;
+  if (launch_gemm(scaled ? EPI_RESADD_SCALED_F32 : EPI_RESADD_F32, g, nullptr) != CS_OK ||
+      sscanf(name, "gemm_kernel<%d, %d", &bm, &bn) != 2 || bn <= 0) return 0;
   const int64_t parts = (N + bn - 1) / bn;
   return parts <= 8 ? (int32_t)parts : 0;
 }
@@ -992,7 +1090,9 @@ cs_status launch_gemm(int epilogue, const GemmArgs& g_in, hipStream_t stream) {
     case EPI_GELU_BF16: return launch_epi<EPI_GELU_BF16>(g, stream);
     case EPI_GELU_F32: return launch_epi<EPI_GELU_F32>(g, stream);
     case EPI_GELU_SPLIT: return launch_epi<EPI_GELU_SPLIT>(g, stream);
-    case EPI_RESADD_F32: return launch_epi<EPI_RESADD_F32>(g, stream);
+    case EPI_RESADD_F32:
+    case EPI_RESADD_SUMS_F32:
+      return g.s1_out ? launch_epi<EPI_RESADD_SUMS_F32>(g, stream) : launch_epi<EPI_RESADD_F32>(g, stream);
     case EPI_RESADD_SCALED_F32:
       if (!g.col_scale || (reinterpret_cast<uintptr_t>(g.col_scale) & 15))
         return fail(CS_ERR_INVALID_ARG, "gemm: the scaled residual epilogue needs a 16-byte aligned col_scale");
