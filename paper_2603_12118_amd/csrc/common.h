@@ -107,6 +107,8 @@ struct GemmArgs {
   // measurement aid: when set (host buffer of at least 96 bytes), launch_gemm writes the name of the kernel
   // instantiation it would run for these arguments there and launches nothing
   char* describe;
+  // set by the launcher: the residual epilogue stores plainly (through the L2's write-back) instead of write-through
+  int32_t plain_stores;
 };
 
 cs_status launch_gemm(int epilogue, const GemmArgs& g, hipStream_t stream);

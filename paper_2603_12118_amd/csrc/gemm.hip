@@ -743,7 +743,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
           store_block<NB, float, true, MFMA16, FOLDS_SUMS>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
-                                       wt && CS_GEMM_RESADD_WT, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr,
+                                       wt && CS_GEMM_RESADD_WT && !g.plain_stores, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr,
                                        folding ? &fold : nullptr);
           if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
@@ -847,7 +847,7 @@ constexpr int CHIP_CUS = 256;
 // L2 read latency and the L1 miss queue full 58 % of the time).
 template <int BM, int BN>
 __device__ __forceinline__ void tile_origin(int id, int tiles_m, int tiles_n, int& m0, int& n0) {
-  constexpr int GROUP_M = 4;
+  constexpr int GROUP_M = 4;   // (2: the same within noise; 8: 1 % slower on the 32-image batch; 16: 4 % slower)
   const int band = id / (GROUP_M * tiles_n), in_band = id - band * (GROUP_M * tiles_n);
   const int band_rows = tiles_m - band * GROUP_M < GROUP_M ? tiles_m - band * GROUP_M : GROUP_M;
   m0 = (band * GROUP_M + in_band % band_rows) * BM;
@@ -950,7 +950,17 @@ static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
     tiles = (g.M / BM) * tiles_n + ((g.M % BM + 63) / 64) * tiles_n;
   if (TAIL == TAIL_SPLIT)   // the tiles of the last round twice, as half tiles
     tiles += tiles % CHIP_CUS;
-  hipLaunchKernelGGL(kern, dim3(tiles, g.splits > 1 ? g.splits : 1), dim3(NT), LDS, stream, g);
+  GemmArgs ga = g;
+  // The residual epilogue's stores are write-through except in launches of the narrow tiles that run more than
+  // one round: there the next round's operand loads queue behind the first round's burst of stores, and stores
+  // that stay in the L2's write-back do better (16 384 tokens: out projection 487 -> 521, down projection
+  // 757 -> 775 TFLOP/s; one round and the 256 x 256 tile: 1 - 4 % worse).  CS_GEMM_RESADD_PLAIN in the environment
+  // (read once) overrides the rule for measurement: 0 never plain, 1 always.
+  {
+    static const int mode = [] { const char* v = getenv("CS_GEMM_RESADD_PLAIN"); return v && *v >= '0' && *v <= '1' ? *v - '0' : 2; }();
+    ga.plain_stores = mode == 1 || (mode == 2 && BN < 256 && tiles > CHIP_CUS);
+  }
+  hipLaunchKernelGGL(kern, dim3(tiles, g.splits > 1 ? g.splits : 1), dim3(NT), LDS, stream, ga);
   CS_HIP(hipGetLastError());
   return CS_OK;
 }
