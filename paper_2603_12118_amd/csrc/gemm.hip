@@ -539,13 +539,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // paid once per chunk (the stores in between keep the compiler from hoisting the loads).  With
   // four waves per workgroup (one per SIMD, or small tiles) the registers for the whole wave tile
   // are free, so every lane fetches the 16-byte pieces it will update before the last K slice.
-  // With eight waves there is room for one row block only: it is fetched before the last K slice,
-  // and each chunk's registers are refilled for the next row block as soon as the chunk is stored.
+  // With eight waves there is room for one row block before the last K slice; the second row block is
+  // requested right behind the K loop, into the registers the operands leave, and from then on the pieces of
+  // row block i + 2 are requested as soon as those of row block i are stored (into the same registers), so two
+  // row blocks of x are in flight all through the epilogue (the narrow tiles: out projection 559 -> 575, down
+  // projection 838 -> 870 TFLOP/s on 8192 tokens; the 256 x 256 tile, whose four row blocks per wave leave no
+  // registers for it, stays with one: with two it spills more and gains nothing).
   constexpr bool RESADD = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SCALED_F32 || EPI == EPI_RESADD_SUMS_F32;
   constexpr bool TWO_PER_SIMD = NWAVES > 4 || (BM == 128 && BN == 160);   // 256 registers per wave, not 512
   constexpr bool HOLD = RESADD && !TWO_PER_SIMD;
   constexpr bool HOLD_ROW = RESADD && TWO_PER_SIMD;
-  [[maybe_unused]] f32x4 held[HOLD ? TM : 1][(HOLD || HOLD_ROW) ? TN : 1][4];
+  constexpr bool HOLD_TWO = HOLD_ROW && TM > 1 && BN < 256;
+  [[maybe_unused]] f32x4 held[HOLD ? TM : HOLD_TWO ? 2 : 1][(HOLD || HOLD_ROW) ? TN : 1][4];
   [[maybe_unused]] auto fetch_old = [&](int i, int j, f32x4 (&dst)[4]) {
     const int r = lane >> 3, c = (lane & 7) * 4;
     int n = n0 + wn * WN + j * 32 + c;
@@ -593,6 +598,12 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
     if constexpr (CONSUMES_NORM) gather_scale();
   });
   if constexpr (CONSUMES_NORM) publish_scale();
+  if constexpr (HOLD_TWO) {
+    if (m0 + wm * WM + 32 < M) {   // wave-uniform
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fetch_old(1, j, held[1][j]);
+    }
+  }
   // producer of a folded RMSNorm: the gain of the tile's columns goes to LDS, from where the epilogue's
   // row-segment lanes read it
   constexpr bool FOLDS_NORM = RESADD;
@@ -743,9 +754,12 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
         const int col0 = nw + j0 * 32;
         if constexpr (RESADD) {
           store_block<NB, float, true, MFMA16, FOLDS_SUMS>(chunk, v, static_cast<float*>(g.out), g.ldo, g.row_map, mrow, M, col0, n_end, true,
-                                       wt && CS_GEMM_RESADD_WT && !g.plain_stores, HOLD ? held[i][j0] : HOLD_ROW ? held[0][j0] : nullptr,
+                                       wt && CS_GEMM_RESADD_WT && !g.plain_stores,
+                                       HOLD ? held[i][j0] : HOLD_TWO ? held[i & 1][j0] : HOLD_ROW ? held[0][j0] : nullptr,
                                        folding ? &fold : nullptr);
-          if constexpr (HOLD_ROW) {
+          if constexpr (HOLD_TWO) {
+            if (i + 2 < TM) fetch_old(i + 2, j0, held[i & 1][j0]);
+          } else if constexpr (HOLD_ROW) {
             if (i + 1 < TM) fetch_old(i + 1, j0, held[0][j0]);
           }
         } else if constexpr (OUT_F32) {
