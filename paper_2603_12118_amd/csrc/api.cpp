@@ -757,6 +757,9 @@ cs_status cs_encoder_step_kernel(const cs_encoder* enc, int32_t step, int64_t n_
       break;
     default: return fail(CS_ERR_INVALID_ARG, "cs_encoder_step_kernel: step must be one of the four GEMM steps of a block");
   }
+  // (an audio tower's residual GEMMs run the instantiation that also writes the plain sums of a folded LayerNorm)
+  if (epi == EPI_RESADD_F32 && c.arch == CS_ARCH_AUDIO && !fold_off() && n_tokens > SPLIT_K_MAX_TOKENS)
+    g.s1_out = reinterpret_cast<float*>(uintptr_t(16));   // describe mode: only looked at, never written
   g.lda = g.K;
   if (epi == EPI_RESADD_SCALED_F32) g.col_scale = enc->ptr<float>(enc->layers[0].ls1);
   // (batches small enough for split K run other launches; this names the kernel of the unsplit path)
