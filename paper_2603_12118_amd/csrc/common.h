@@ -79,9 +79,9 @@ struct GemmArgs {
   float q_scale;
   // RMSNorm folded into the GEMMs on both sides of it (y = (x g / rms) W^T + b = (1/rms) ((x g) W^T) + b: a
   // row scale commutes with the product, and bf16(x g) carries the same relative rounding as bf16(x g / rms)).
-  //  producer (EPI_RESADD_F32 on the four-wave 256 x 160 tile): with ss_out set, the epilogue also writes
-  //    xg[m, n] = bf16(x_new[m, n] * norm_gain[n]) and ss_out[(n0 / 160) * ss_stride + m] = the sum of
-  //    x_new[m, n]^2 over the tile's columns;
+  //  producer (the residual epilogues, on any tile of at most 256 columns): with ss_out set, the epilogue also
+  //    writes xg[m, n] = bf16(x_new[m, n] * norm_gain[n]) and ss_out[(n0 / BN) * ss_stride + m] = the sum of
+  //    x_new[m, n]^2 over the tile's BN columns (gemm_norm_fold_parts tells how many column tiles there are);
   //  consumer (EPI_QKV, EPI_SWIGLU_BF16): with ss_in set, row m of A W^T is multiplied by
   //    rsqrt(sum over ss_parts of ss_in[p * ss_stride + m] / norm_dim + norm_eps) before the bias is added.
   // LayerNorm folds the same way: LN(x) W^T + b = rs ((x g) W^T - mu c) + d with rs = 1/sqrt(var + eps),
