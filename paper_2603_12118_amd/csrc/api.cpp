@@ -444,6 +444,7 @@ struct Workspace {
   size_t s1 = 0;              // LayerNorm towers: per-row partial plain sums, laid out like ss
   int fold_proj, fold_down;   // column tiles of the two residual GEMMs when they fold the next RMSNorm (0: they do not)
   bool split_k;   // small batches: the residual GEMMs run split over K into `parts`
+  int s_proj = 1, s_down = 1;   // ... the out projection and the down projection into so many
 };
 
 // Residual GEMMs of small batches (few workgroups, long K loops) are split over K: up to this many parts
@@ -506,10 +507,18 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   // RMSNorm folded into the GEMMs around it (vision tower, unsplit residual GEMMs): per-row partial sums of
   // squares, one per column tile of the residual GEMM
   w.ss_stride = round_up(N, 64);
-  const bool fold = !w.split_k && !fold_off();
+  // (a residual GEMM that runs split over K leaves its partial sums to the normalisation kernel: no fold)
   const bool ln = c.arch != CS_ARCH_VIT, scaled = c.arch == CS_ARCH_VIT_CLS;
-  w.fold_proj = fold ? gemm_norm_fold_parts(N, D, D, scaled, ln) : 0;
-  w.fold_down = fold ? gemm_norm_fold_parts(N, D, e->I_pad, scaled, ln) : 0;
+  w.s_proj = w.split_k ? k_parts(N, D, D) : 1;
+  w.s_down = w.split_k ? k_parts(N, D, e->I_pad) : 1;
+  // The out projection's short K loop is not split once 128 x 160 tiles fill half the chip: unsplit, the launch
+  // folds the next RMSNorm into its epilogue, which saves more than the split gains (2048 tokens: 5.33 -> 5.19 ms
+  // per step; 1024 tokens: 4.01 -> 4.29 ms, so those stay split).
+  if (w.s_proj > 1 && c.arch == CS_ARCH_VIT && D % 160 == 0 && ((N + 127) / 128) * (D / 160) >= 128 && !fold_off() &&
+      gemm_norm_fold_parts(N, D, D, scaled, ln) > 0)
+    w.s_proj = 1;
+  w.fold_proj = w.s_proj == 1 && !fold_off() ? gemm_norm_fold_parts(N, D, D, scaled, ln) : 0;
+  w.fold_down = w.s_down == 1 && !fold_off() ? gemm_norm_fold_parts(N, D, e->I_pad, scaled, ln) : 0;
   w.ss = take((w.fold_proj || w.fold_down) ? (size_t)8 * w.ss_stride * 4 : 0);
   w.s1 = take(ln && (w.fold_proj || w.fold_down) ? (size_t)8 * w.ss_stride * 4 : 0);
   w.total = off;
@@ -913,10 +922,9 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     folded = 0;
   };
   auto gemm_residual = [&](const bf16_t* A, int64_t lda, size_t W, size_t bias, size_t scale, int64_t K, size_t next_gain,
-                           int fold_parts) -> cs_status {
+                           int fold_parts, int S) -> cs_status {
     GemmArgs g = {};
     g.A = A; g.lda = lda; g.W = e->ptr<bf16_t>(W); g.ldo = D; g.M = (int32_t)N; g.N = (int32_t)D;
-    const int S = w.split_k ? k_parts(N, D, K) : 1;
     if (S > 1) {
       g.ldw = K; g.K = (int32_t)(K / S); g.splits = S; g.split_stride = N * D; g.out = parts;
       if (cs_status st = launch_gemm(EPI_F32, g, stream)) return st;
@@ -1000,7 +1008,7 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
     }
     {
       StepTimer tm(e, CS_STEP_PROJ, stream);
-      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D, L.g2, w.fold_proj)) return st;
+      if (cs_status st = gemm_residual(attn, D, L.wo, L.bo, cls ? L.ls1 : 0, D, L.g2, w.fold_proj, w.s_proj)) return st;
     }
     if (cs_status st = norm(L.g2, L.be2)) return st;
     {
@@ -1024,7 +1032,7 @@ static cs_status encode_impl(cs_encoder* e, const void* patches, const int32_t* 
       StepTimer tm(e, CS_STEP_MLP_DOWN, stream);
       // (the norm behind the last block is the merger's, which splits its output: a kernel of its own)
       const size_t next_g1 = l + 1 < c.n_layers ? e->layers[l + 1].g1 : 0;
-      if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad, next_g1, w.fold_down)) return st;
+      if (cs_status st = gemm_residual(big, e->I_pad, L.w2, L.b2, cls ? L.ls2 : 0, e->I_pad, next_g1, w.fold_down, w.s_down)) return st;
     }
   }
 

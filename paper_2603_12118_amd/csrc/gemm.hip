@@ -1017,6 +1017,14 @@ static int resadd_pair_mode() {
   return mode;
 }
 
+static bool small_resadd_pair() {
+  static const bool on = [] {
+    const char* v = getenv("CS_GEMM_SMALL_PAIR");
+    return !(v && *v == '0');
+  }();
+  return on;
+}
+
 static bool narrow_resadd() {
   static const bool on = [] {
     const char* v = getenv("CS_GEMM_NARROW_RESADD");
@@ -1076,6 +1084,14 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
     // 128 x 128 tiles; at 120 workgroups it loses)
     if (big >= 160 && big <= 256 && big_ok) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
+#if CS_GEMM_MFMA16
+  // a residual GEMM with N = 1280 too small for the tiles above: 128 x 160 tiles rather than 128 x 128, which makes
+  // eight column tiles instead of ten, so the next RMSNorm still folds into it (4096 tokens: 8.32 -> 7.77 ms per
+  // step; CS_GEMM_SMALL_PAIR=0 in the environment keeps the 128 x 128 tiles, for measurement)
+  if constexpr (EPI == EPI_RESADD_F32) {
+    if (g.N % 160 == 0 && g.splits <= 1 && small_resadd_pair()) return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
+  }
+#endif
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
 }
 
