@@ -1017,6 +1017,20 @@ static int resadd_pair_mode() {
   return mode;
 }
 
+// The fewest 256 x 256 tiles beyond one round of the chip for which a launch takes that tile: 257.  With the half
+// tiles of a split last round such a launch never runs below 2/3 full (257 tiles: a round and a half round),
+// which beats what the 128 x 128 tiles lose inside the CU (3072 tokens: gate|up 731 -> 872 TFLOP/s, the step 7.30
+// -> 6.98 ms; 6144 tokens: 10.74 -> 10.33 ms).  CS_GEMM_BIG_MIN in the environment (read once) sets another
+// threshold for measurement; 384, a round and a half, was the rule before the half tiles existed.
+static int64_t big_tile_min() {
+  static const int64_t v = [] {
+    const char* e = getenv("CS_GEMM_BIG_MIN");
+    const long x = e ? atol(e) : 0;
+    return (int64_t)(x > 256 && x <= 4096 ? x : 257);
+  }();
+  return v;
+}
+
 static bool small_resadd_pair() {
   static const bool on = [] {
     const char* v = getenv("CS_GEMM_SMALL_PAIR");
@@ -1048,10 +1062,12 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   }
 #endif
   if constexpr (EIGHT_WAVES_OK) {
-    // 256 x 256 for a round and a half of the chip or more (CS_GEMM_NARROW_RESADD=1 in the environment makes the
+    // 256 x 256 for more than a round of the chip (CS_GEMM_NARROW_RESADD=1 in the environment makes the
     // residual add take the narrow tile below at any size, for measurement: the 32-image batch 166.5 -> 177.4 ms)
     const bool narrow_first = EPI == EPI_RESADD_F32 && g.N % 160 == 0 && narrow_resadd();
-    if (big >= 384 && big_ok && !narrow_first) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
+    // (the residual GEMMs keep a round and a half: below it their narrow tiles make whole rounds, e.g. two at 16 384 tokens)
+    constexpr bool RES = EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SUMS_F32;
+    if (big >= (RES ? 384 : big_tile_min()) && big_ok && !narrow_first) return launch_cfg<256, 256, 2, 4, EPI>(g, stream);
   }
   if constexpr (EPI != EPI_QKV && EPI != EPI_SWIGLU_BF16) {
     // narrow outputs (N = hidden = 1280): 256 x 160 tiles, four waves of 64 x 160, give M/256 * 8
