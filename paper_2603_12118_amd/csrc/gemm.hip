@@ -1031,12 +1031,12 @@ static int64_t big_tile_min() {
   return v;
 }
 
-static bool small_resadd_pair() {
-  static const bool on = [] {
+static int small_resadd_pair() {
+  static const int mode = [] {
     const char* v = getenv("CS_GEMM_SMALL_PAIR");
-    return !(v && *v == '0');
+    return v && *v >= '0' && *v <= '2' ? *v - '0' : 2;
   }();
-  return on;
+  return mode;
 }
 
 static bool narrow_resadd() {
@@ -1103,9 +1103,16 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
 #if CS_GEMM_MFMA16
   // a residual GEMM with N = 1280 too small for the tiles above: 128 x 160 tiles rather than 128 x 128, which makes
   // eight column tiles instead of ten, so the next RMSNorm still folds into it (4096 tokens: 8.32 -> 7.77 ms per
-  // step; CS_GEMM_SMALL_PAIR=0 in the environment keeps the 128 x 128 tiles, for measurement)
+  // step).  Up to one tile per CU they run with eight waves of 32 x 80, so that every SIMD has two waves to
+  // alternate between (3072 tokens: 6.91 -> 6.73 ms, 4096: 7.58 -> 7.44); beyond that with four waves of 64 x 80,
+  // two workgroups per CU.  CS_GEMM_SMALL_PAIR in the environment, for measurement: 0 keeps the 128 x 128 tiles,
+  // 1 takes four waves at any size.
   if constexpr (EPI == EPI_RESADD_F32) {
-    if (g.N % 160 == 0 && g.splits <= 1 && small_resadd_pair()) return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
+    if (g.N % 160 == 0 && g.splits <= 1 && small_resadd_pair() > 0) {
+      const int64_t tiles = ((g.M + 127) / 128) * (g.N / 160);
+      if (small_resadd_pair() == 2 && tiles <= CHIP_CUS) return launch_cfg<128, 160, 4, 2, EPI>(g, stream);
+      return launch_cfg<128, 160, 2, 2, EPI>(g, stream);
+    }
   }
 #endif
   return launch_cfg<128, 128, 2, 2, EPI>(g, stream);
