@@ -170,7 +170,8 @@ def main() -> int:
         evs[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
-    ev_ms = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    ev_raw = [evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)]
+    ev_ms = sorted(ev_raw)
     dom_ms, dom_n = enc.cs_encoder_read_timing()
     enc.cs_encoder_time_step(0)
     enc.cs_encoder_time_every(1)
@@ -202,7 +203,7 @@ def main() -> int:
         "metric": "encoder_patches_per_s" if w.cfg.arch != "audio" else "encoder_mel_frames_per_s",
         "value": n_in / (ms * 1e-3), "unit": "patches/s" if w.cfg.arch != "audio" else "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "ms_per_step_median_hip_events": ev_ms[len(ev_ms) // 2], "ms_per_step_min_hip_events": ev_ms[0],
+        "ms_per_step_median_hip_events": ev_ms[len(ev_ms) // 2], "ms_per_step_min_hip_events": ev_ms[0], "ms_per_step_max_hip_events": ev_ms[-1], "slowest_step": ev_raw.index(ev_ms[-1]),
         "host_us_per_call_median": host_us[len(host_us) // 2], "plan_cache": {"hits": plan_hits, "misses": plan_misses},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "launch": "hip graph replay" if args.graph else "eager", "items": w.n_items, "input_rows": n_in, "embedding_rows": int(n_out),

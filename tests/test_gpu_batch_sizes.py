@@ -78,3 +78,27 @@ def test_audio_clip_lengths(n_clips, frames):
     w = wl.audio_workload(f"audio_{n_clips}x{frames}", wl.audio_config(2), n_clips, frames, seq_len=2048, data_seed=frames)
     W = shared_weights("audio", w)
     check_items(f"audio {n_clips} clips of {frames} frames", w, W, sorted({0, n_clips - 1}))
+
+
+def test_tile_choice_by_batch_size():
+    """The launcher's choices the batches above straddle, by name: which instantiation the four GEMMs of a block
+    run for a number of tokens (`gemm_kernel<BM, BN, waves along M, waves along N, epilogue, tail>`)."""
+    w = wl.images_workload("tiles_by_size", replace(wl.vit_7b_config(2), dtype="bf16", full_attn_layers=(1,)),
+                           [(56, 56)], seq_len=8192, data_seed=1)
+    enc = B.Encoder(w.cfg, shared_weights("vit", w))
+    name = lambda step, n: enc.cs_encoder_step_kernel(B.STEPS[step], n).split(">")[0] + ">"
+    # gate|up: 128 x 128 below a round of 256 x 256 tiles (short of 5/8 of it), 256 x 256 from 160 tiles on, with half
+    # tiles in a last round that is at most half full
+    assert name("mlp_up", 1024) == "gemm_kernel<128, 128, 2, 2, 5, 0>"
+    assert name("mlp_up", 2048) == "gemm_kernel<256, 256, 2, 4, 5, 0>"      # 216 tiles: one round
+    assert name("mlp_up", 3072) == "gemm_kernel<256, 256, 2, 4, 5, 2>"      # 324 tiles: a round and 68
+    assert name("mlp_up", 8192) == "gemm_kernel<256, 256, 2, 4, 5, 2>"      # 864 tiles: three rounds and 96
+    # residual GEMMs with N = 1280: 128 x 160 (eight waves up to one tile per CU, then two four-wave workgroups per
+    # CU), 256 x 160 from 192 of those on, 256 x 256 from a round and a half on
+    assert name("proj", 3072) == "gemm_kernel<128, 160, 4, 2, 4, 0>"
+    assert name("proj", 5120) == "gemm_kernel<128, 160, 2, 2, 4, 0>"
+    assert name("proj", 8192) == "gemm_kernel<256, 160, 4, 2, 4, 0>"
+    assert name("mlp_down", 8192) == "gemm_kernel<256, 160, 4, 2, 4, 0>"
+    assert name("proj", 24576) == "gemm_kernel<256, 256, 2, 4, 4, 0>"        # 480 tiles: a round and 224
+    assert name("proj", 32768) == "gemm_kernel<256, 256, 2, 4, 4, 2>"        # 640 tiles: two rounds and 128
+    assert name("qkv", 8192) == "gemm_kernel<256, 256, 2, 4, 6, 0>"
