@@ -78,8 +78,8 @@ __device__ __forceinline__ float silu_f(float z) {
 // 16 bytes per lane.  LDS serves one wave's instructions in order, so no wait is needed between a
 // chunk's writes and reads beyond keeping the compiler from reordering them.
 // What a tile may use behind its two stage buffers: 1 KB of per-column values, then the waves' per-row partial
-// sums of a folded normalisation, [2][WGN][BM] floats (sums of squares, plain sums).  (The four-wave 128 x 160
-// tile, which must fit a CU twice, keeps room for one of the two and folds RMSNorm only.)
+// sums of a folded normalisation, [2][WGN][BM] floats (sums of squares, plain sums).  (The 128 x 160 tiles, of
+// which the four-wave one must fit a CU twice, have 128 rows and two waves along N: 2 KB of sums.)
 constexpr int EXTRA_LDS_BYTES = 1024 + 2 * 4 * 256 * 4;
 constexpr int EXTRA_LDS_BYTES_PAIR = 1024 + 4 * 256 * 4;
 template <int BM, int BN>
@@ -1104,12 +1104,12 @@ static cs_status launch_epi(const GemmArgs& g, hipStream_t stream) {
   }
 #if CS_GEMM_MFMA16
   // a residual GEMM with N = 1280 too small for the tiles above: 128 x 160 tiles rather than 128 x 128, which makes
-  // eight column tiles instead of ten, so the next RMSNorm still folds into it (4096 tokens: 8.32 -> 7.77 ms per
-  // step).  Up to one tile per CU they run with eight waves of 32 x 80, so that every SIMD has two waves to
+  // eight column tiles instead of ten, so the next normalisation still folds into it (vision tower, 4096 tokens:
+  // 8.32 -> 7.77 ms per step; audio tower, 3000 tokens: 8.08 -> 7.94 ms).  Up to one tile per CU they run with eight waves of 32 x 80, so that every SIMD has two waves to
   // alternate between (3072 tokens: 6.91 -> 6.73 ms, 4096: 7.58 -> 7.44); beyond that with four waves of 64 x 80,
   // two workgroups per CU.  CS_GEMM_SMALL_PAIR in the environment, for measurement: 0 keeps the 128 x 128 tiles,
   // 1 takes four waves at any size.
-  if constexpr (EPI == EPI_RESADD_F32) {
+  if constexpr (EPI == EPI_RESADD_F32 || EPI == EPI_RESADD_SUMS_F32) {
     if (g.N % 160 == 0 && g.splits <= 1 && small_resadd_pair() > 0) {
       const int64_t tiles = ((g.M + 127) / 128) * (g.N / 160);
       if (small_resadd_pair() == 2 && tiles <= CHIP_CUS) return launch_cfg<128, 160, 4, 2, EPI>(g, stream);
