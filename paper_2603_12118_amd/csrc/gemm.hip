@@ -84,6 +84,19 @@ constexpr int EXTRA_LDS_BYTES = 1024 + 2 * 4 * 256 * 4;
 constexpr int EXTRA_LDS_BYTES_PAIR = 1024 + 4 * 256 * 4;
 template <int BM, int BN>
 constexpr int extra_lds_bytes() { return BM == 128 && BN == 160 ? EXTRA_LDS_BYTES_PAIR : EXTRA_LDS_BYTES; }
+// Stage buffers of the K loop.  Two everywhere (a slice's MFMAs cover the next slice's loads where the tile is
+// large, and more would not fit) except on the eight-wave 128 x 160 tile, which runs one workgroup per CU in
+// launches that do not fill the chip: its slice of MFMAs is much shorter than the loads' latency, so it keeps
+// CS_GEMM_SMALL_STAGES - 1 slices in flight, four stages being what 160 KB of LDS hold (build-time switch for
+// measurement: 2 is the plain double buffer.  Measured on one box, 3072 tokens, 2 / 3 / 4 stages: out projection
+// 31.4 / 32.1 / 28.5 us, down projection 60.3 / 61.8 / 52.0 us, the step 6.78 / 6.85 / 6.40 ms).
+#ifndef CS_GEMM_SMALL_STAGES
+#define CS_GEMM_SMALL_STAGES 4
+#endif
+template <int BM, int BN, int NWAVES>
+constexpr int stages() { return BM == 128 && BN == 160 && NWAVES == 8 ? CS_GEMM_SMALL_STAGES : 2; }
+template <int BM, int BN, int NWAVES>
+constexpr int tile_lds_bytes() { return stages<BM, BN, NWAVES>() * (BM + BN) * 128 + extra_lds_bytes<BM, BN>(); }
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
@@ -357,6 +370,51 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
     bp[i] = g.W + (int64_t)r * g.ldw + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
   }
   const int KT = K >> 6;
+  constexpr int STAGES = stages<BM, BN, NWAVES>();
+  if constexpr (STAGES > 2) {
+    // Slices kt + 1 .. kt + STAGES - 2 stay in flight while slice kt is consumed.  A wave's loads complete in the
+    // order it issued them, so waiting until at most n * L of them are outstanding (L = its loads per slice) means
+    // everything older than the newest n slices has landed.
+    const int L = A_LOADS + (BN % (8 * NWAVES) == 0 || ((B_LOADS - 1) * NWAVES + wave) * 8 < BN ? B_LOADS : B_LOADS - 1);
+    static_assert(STAGES <= 4, "the waits below cover up to two slices in flight");
+    auto wait_newer = [&](int n) {   // n newer slices may still be in flight
+      if (n <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      else if (L == A_LOADS + B_LOADS) {
+        if (n == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_LOADS + B_LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (A_LOADS + B_LOADS)) : "memory");
+      } else {
+        if (n == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_LOADS + B_LOADS - 1) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (A_LOADS + B_LOADS - 1)) : "memory");
+      }
+    };
+    static_assert(2 * (A_LOADS + B_LOADS) < 64, "vmcnt is a 6-bit counter");
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+      if (st < KT) issue_slice<A_LOADS, B_LOADS, NWAVES, BM, BN>(ap, bp, st, smem + st * STAGE_BYTES, wave);
+    int cur_s = 0;                     // stage of slice kt
+    for (int kt = 0; kt < KT - 1; ++kt) {
+      const int ahead = KT - 1 - kt < STAGES - 2 ? KT - 1 - kt : STAGES - 2;   // newer slices already requested
+      wait_newer(ahead);               // this wave's part of slice kt has landed
+      // ... and everyone's; slice kt-1 fully consumed, so its stage is free.  A bare barrier: __syncthreads()
+      // carries a fence that waits for every outstanding load, the newer slices' included.
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      const unsigned char* cur = smem + cur_s * STAGE_BYTES;
+      const int nxt_s = cur_s == 0 ? STAGES - 1 : cur_s - 1;   // the stage slice kt-1 was in = that of slice kt + STAGES - 1
+      if (kt + STAGES - 1 < KT)
+        k_slice<BM, BN, WGM, WGN, W_FIRST, true>(ap, bp, kt + STAGES - 1, cur, smem + nxt_s * STAGE_BYTES, a_rd, b_rd, sw, lhi, wave, acc);
+      else
+        k_slice<BM, BN, WGM, WGN, W_FIRST, false>(ap, bp, 0, cur, nullptr, a_rd, b_rd, sw, lhi, wave, acc);
+      cur_s = cur_s + 1 == STAGES ? 0 : cur_s + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    before_last();
+    k_slice<BM, BN, WGM, WGN, W_FIRST, false>(ap, bp, 0, smem + ((KT - 1) % STAGES) * STAGE_BYTES, nullptr, a_rd, b_rd, sw, lhi,
+                                              wave, acc);
+    return;
+  }
   issue_slice<A_LOADS, B_LOADS, NWAVES, BM, BN>(ap, bp, 0, smem, wave);
   for (int kt = 0; kt < KT - 1; ++kt) {
     const unsigned char* cur = smem + (kt & 1) * STAGE_BYTES;
@@ -386,7 +444,7 @@ constexpr bool light_tail() {
 
 // One output tile: K loop and epilogue.
 // LDS_ALLOC: bytes of LDS the launch has (that of its largest tile shape).
-template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>
+template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = tile_lds_bytes<BM, BN, WGM * WGN>()>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
@@ -400,7 +458,9 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // narrow launch) they go behind everything else this tile uses, inside what the launch's main tile shape allocated
   constexpr bool CHUNKS_BEHIND = NWAVES * CHUNK_BYTES > STAGE_BYTES;
   constexpr int XTRA = extra_lds_bytes<BM, BN>();
-  static_assert(!CHUNKS_BEHIND || (2 * STAGE_BYTES + XTRA + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
+  constexpr int STAGES = stages<BM, BN, NWAVES>();
+  static_assert(STAGES == 2 || EPI != EPI_QKV, "the rotary table's place assumes two stage buffers");
+  static_assert(!CHUNKS_BEHIND || (STAGES * STAGE_BYTES + XTRA + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
                 "no room for the epilogue chunks");
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -409,7 +469,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // The extra LDS behind the stage buffers.  Consumer of a folded normalisation: BM row scales, BM row shifts
   // (LayerNorm: mean times scale) and BN column values of norm_shift.  Producer: the gain of the tile's columns
   // and, from float 256 on, the waves' sums of squares [WGN][BM] and plain sums [WGN][BM].
-  float* extra_lds = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
+  float* extra_lds = reinterpret_cast<float*>(smem + STAGES * STAGE_BYTES);
   // consumer: thread t < BM gathers the partial sums of squares of row m0 + t while the last K slice runs
   // (thread BM + t the partial plain sums, for a LayerNorm), they are turned into 1 / rms (or 1 / sigma and
   // mean / sigma) behind the K loop and left in LDS for every wave
@@ -483,8 +543,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
 
   f32x16 acc[TM][TN];
   // this wave's epilogue chunk, in the stage buffer the last K slice did not use
-  unsigned char* chunk = CHUNKS_BEHIND ? smem + 2 * STAGE_BYTES + XTRA + wave * CHUNK_BYTES
-                                       : smem + ((g.K >> 6) & 1) * STAGE_BYTES + wave * CHUNK_BYTES;
+  unsigned char* chunk = CHUNKS_BEHIND ? smem + STAGES * STAGE_BYTES + XTRA + wave * CHUNK_BYTES
+                                       : smem + ((g.K >> 6) % STAGES) * STAGE_BYTES + wave * CHUNK_BYTES;
 
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= 2 * g.hidden) {
@@ -901,7 +961,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
       m0 += (t & 1) * (BM / 2);
       if (m0 >= M) return;   // the lower half of a tile of a ragged last tile row may be empty
-      tile_body<BM / 2, BN, WGM, WGN, EPI, 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>(g, smem, m0, n0);
+      tile_body<BM / 2, BN, WGM, WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN>()>(g, smem, m0, n0);
       return;
     }
     nb = n_main;
@@ -911,7 +971,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI, 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -944,7 +1004,7 @@ static bool tail_split_off() {
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = 2 * (BM + BN) * 128 + extra_lds_bytes<BM, BN>();
+  constexpr int LDS = tile_lds_bytes<BM, BN, WGM * WGN>();
   static_assert(LDS <= 160 * 1024, "LDS of a CU");
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
