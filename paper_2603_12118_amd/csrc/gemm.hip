@@ -82,8 +82,19 @@ __device__ __forceinline__ float silu_f(float z) {
 // which the four-wave one must fit a CU twice, have 128 rows and two waves along N: 2 KB of sums.)
 constexpr int EXTRA_LDS_BYTES = 1024 + 2 * 4 * 256 * 4;
 constexpr int EXTRA_LDS_BYTES_PAIR = 1024 + 4 * 256 * 4;
-template <int BM, int BN>
-constexpr int extra_lds_bytes() { return BM == 128 && BN == 160 ? EXTRA_LDS_BYTES_PAIR : EXTRA_LDS_BYTES; }
+// (Build-time switch for measurement: -DCS_GEMM_NARROW_STAGES=3 gives the eight-wave 256 x 160 tile of the plain
+// residual epilogue a third stage buffer, see stages(); what is left of 160 KB then holds exactly its column
+// values and one set of sums.  Measured on one box, alternated: slower, down projection 885 -> 816 TFLOP/s, the
+// 8-image step 11.72 -> 12.02 ms, the 16 384-token step 26.35 -> 26.6 ms.)
+#ifndef CS_GEMM_NARROW_STAGES
+#define CS_GEMM_NARROW_STAGES 2
+#endif
+template <int BM, int BN, int NWAVES, int EPI>
+constexpr bool third_stage() { return CS_GEMM_NARROW_STAGES == 3 && BM == 256 && BN == 160 && NWAVES == 8 && EPI == EPI_RESADD_F32; }
+template <int BM, int BN, int NWAVES = 0, int EPI = -1>
+constexpr int extra_lds_bytes() {
+  return third_stage<BM, BN, NWAVES, EPI>() ? 1024 + 2 * 256 * 4 : BM == 128 && BN == 160 ? EXTRA_LDS_BYTES_PAIR : EXTRA_LDS_BYTES;
+}
 // Stage buffers of the K loop.  Two everywhere (a slice's MFMAs cover the next slice's loads where the tile is
 // large, and more would not fit) except on the eight-wave 128 x 160 tile, which runs one workgroup per CU in
 // launches that do not fill the chip: its slice of MFMAs is much shorter than the loads' latency, so it keeps
@@ -93,10 +104,10 @@ constexpr int extra_lds_bytes() { return BM == 128 && BN == 160 ? EXTRA_LDS_BYTE
 #ifndef CS_GEMM_SMALL_STAGES
 #define CS_GEMM_SMALL_STAGES 4
 #endif
-template <int BM, int BN, int NWAVES>
-constexpr int stages() { return BM == 128 && BN == 160 && NWAVES == 8 ? CS_GEMM_SMALL_STAGES : 2; }
-template <int BM, int BN, int NWAVES>
-constexpr int tile_lds_bytes() { return stages<BM, BN, NWAVES>() * (BM + BN) * 128 + extra_lds_bytes<BM, BN>(); }
+template <int BM, int BN, int NWAVES, int EPI>
+constexpr int stages() { return BM == 128 && BN == 160 && NWAVES == 8 ? CS_GEMM_SMALL_STAGES : third_stage<BM, BN, NWAVES, EPI>() ? 3 : 2; }
+template <int BM, int BN, int NWAVES, int EPI>
+constexpr int tile_lds_bytes() { return stages<BM, BN, NWAVES, EPI>() * (BM + BN) * 128 + extra_lds_bytes<BM, BN, NWAVES, EPI>(); }
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
@@ -324,7 +335,7 @@ __device__ __forceinline__ void k_slice(const bf16_t* const* ap, const bf16_t* c
 // passed the last barrier after reading it and nothing was loaded into it since.
 // before_last() runs between the last barrier and the last slice's MFMAs: global loads it issues
 // are in flight while those execute.
-template <int BM, int BN, int WGM, int WGN, bool W_FIRST, typename F>
+template <int BM, int BN, int WGM, int WGN, bool W_FIRST, int STAGES, typename F>
 __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem, int m0, int n0,
                                           f32x16 (&acc)[BM / WGM / 32][(BN / WGN + 31) / 32], F&& before_last) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -370,7 +381,6 @@ __device__ __forceinline__ void main_loop(const GemmArgs& g, unsigned char* smem
     bp[i] = g.W + (int64_t)r * g.ldw + (((lane & 7) ^ ((rt >> 1) & 7)) << 3);
   }
   const int KT = K >> 6;
-  constexpr int STAGES = stages<BM, BN, NWAVES>();
   if constexpr (STAGES > 2) {
     // Slices kt + 1 .. kt + STAGES - 2 stay in flight while slice kt is consumed.  A wave's loads complete in the
     // order it issued them, so waiting until at most n * L of them are outstanding (L = its loads per slice) means
@@ -444,7 +454,7 @@ constexpr bool light_tail() {
 
 // One output tile: K loop and epilogue.
 // LDS_ALLOC: bytes of LDS the launch has (that of its largest tile shape).
-template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = tile_lds_bytes<BM, BN, WGM * WGN>()>
+template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = tile_lds_bytes<BM, BN, WGM * WGN, EPI>()>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
@@ -457,8 +467,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // the epilogue chunks live in the idle stage buffer; where that is too small for them (a 64-row tail tile of a
   // narrow launch) they go behind everything else this tile uses, inside what the launch's main tile shape allocated
   constexpr bool CHUNKS_BEHIND = NWAVES * CHUNK_BYTES > STAGE_BYTES;
-  constexpr int XTRA = extra_lds_bytes<BM, BN>();
-  constexpr int STAGES = stages<BM, BN, NWAVES>();
+  constexpr int XTRA = extra_lds_bytes<BM, BN, NWAVES, EPI>();
+  constexpr int STAGES = stages<BM, BN, NWAVES, EPI>();
   static_assert(STAGES == 2 || EPI != EPI_QKV, "the rotary table's place assumes two stage buffers");
   static_assert(!CHUNKS_BEHIND || (STAGES * STAGE_BYTES + XTRA + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
                 "no room for the epilogue chunks");
@@ -553,7 +563,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
       // rows of the transposed v buffer, 64 tokens of one dimension per chunk row.  With the roles of
       // the operands swapped the two halves of a 16x16x32 group index swap too (vsub).
       float bv[TN][4];
-      main_loop<BM, BN, WGM, WGN, false>(g, smem, m0, n0, acc, [&] {
+      main_loop<BM, BN, WGM, WGN, false, STAGES>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -633,7 +643,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   constexpr int CQ = MFMA16 ? 2 : 4;
   f32x4 bias_r[TN][CQ];
   [[maybe_unused]] f32x4 scale_r[EPI == EPI_RESADD_SCALED_F32 ? TN : 1][CQ];
-  main_loop<BM, BN, WGM, WGN, true>(g, smem, m0, n0, acc, [&] {
+  main_loop<BM, BN, WGM, WGN, true, STAGES>(g, smem, m0, n0, acc, [&] {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -961,7 +971,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
       tile_origin<BM, BN>(n_main + (t >> 1), tiles_m, tiles_n, m0, n0);
       m0 += (t & 1) * (BM / 2);
       if (m0 >= M) return;   // the lower half of a tile of a ragged last tile row may be empty
-      tile_body<BM / 2, BN, WGM, WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN>()>(g, smem, m0, n0);
+      tile_body<BM / 2, BN, WGM, WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN, EPI>()>(g, smem, m0, n0);
       return;
     }
     nb = n_main;
@@ -971,7 +981,7 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN, EPI>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -1004,7 +1014,7 @@ static bool tail_split_off() {
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = tile_lds_bytes<BM, BN, WGM * WGN>();
+  constexpr int LDS = tile_lds_bytes<BM, BN, WGM * WGN, EPI>();
   static_assert(LDS <= 160 * 1024, "LDS of a CU");
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
