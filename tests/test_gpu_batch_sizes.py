@@ -83,6 +83,9 @@ def test_audio_clip_lengths(n_clips, frames):
 def test_tile_choice_by_batch_size():
     """The launcher's choices the batches above straddle, by name: which instantiation the four GEMMs of a block
     run for a number of tokens (`gemm_kernel<BM, BN, waves along M, waves along N, epilogue, tail>`)."""
+    import os
+    if any(k.startswith("CS_GEMM_") or k == "CS_NO_NORM_FOLD" for k in os.environ):
+        pytest.skip("a measurement switch in the environment changes the choices this test names")
     w = wl.images_workload("tiles_by_size", replace(wl.vit_7b_config(2), dtype="bf16", full_attn_layers=(1,)),
                            [(56, 56)], seq_len=8192, data_seed=1)
     enc = B.Encoder(w.cfg, shared_weights("vit", w))
