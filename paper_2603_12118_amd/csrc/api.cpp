@@ -767,7 +767,8 @@ cs_status cs_encoder_step_kernel(const cs_encoder* enc, int32_t step, int64_t n_
     default: return fail(CS_ERR_INVALID_ARG, "cs_encoder_step_kernel: step must be one of the four GEMM steps of a block");
   }
   // (an audio tower's residual GEMMs run the instantiation that also writes the plain sums of a folded LayerNorm)
-  if (epi == EPI_RESADD_F32 && c.arch == CS_ARCH_AUDIO && !fold_off() && n_tokens > SPLIT_K_MAX_TOKENS)
+  if (epi == EPI_RESADD_F32 && c.arch == CS_ARCH_AUDIO && !fold_off() &&
+      (n_tokens > SPLIT_K_MAX_TOKENS || k_parts(n_tokens, D, g.K) == 1))
     g.s1_out = reinterpret_cast<float*>(uintptr_t(16));   // describe mode: only looked at, never written
   g.lda = g.K;
   if (epi == EPI_RESADD_SCALED_F32) g.col_scale = enc->ptr<float>(enc->layers[0].ls1);
