@@ -513,7 +513,7 @@ static Workspace layout_workspace(const cs_encoder* e, const BatchPlan& p) {
   w.s_down = w.split_k ? k_parts(N, D, e->I_pad) : 1;
   // The out projection's short K loop is not split once 128 x 160 tiles fill half the chip: unsplit, the launch
   // folds the next RMSNorm into its epilogue, which saves more than the split gains (2048 tokens: 5.33 -> 5.19 ms
-  // per step; 1024 tokens: 4.01 -> 4.29 ms, so those stay split).
+  // per step; 1024 tokens: 3.95 -> 4.00 ms, so those stay split).
   if (w.s_proj > 1 && c.arch == CS_ARCH_VIT && D % 160 == 0 && ((N + 127) / 128) * (D / 160) >= 128 && !fold_off() &&
       gemm_norm_fold_parts(N, D, D, scaled, ln) > 0)
     w.s_proj = 1;
