@@ -197,7 +197,14 @@ def main() -> int:
     # (a replayed graph carries no timing events: the dominant kernel is then not timed)
     dom_tflops = dom_flops / (dom_avg_ms * 1e-3) / 1e12 if dom_n > 0 else None
 
-    kernel = enc.cs_encoder_step_kernel(B.STEPS[dominant], int(w.cu_seqlens[-1]) // (2 if w.cfg.arch == "audio" else 1))
+    # transformer tokens of the batch: two mel frames per token; a class-token tower adds four rows per tile
+    # (class token and three of padding)
+    n_tokens = int(w.cu_seqlens[-1])
+    if w.cfg.arch == "audio":
+        n_tokens //= 2
+    elif w.cfg.arch == "vit_cls":
+        n_tokens += 4 * w.n_items
+    kernel = enc.cs_encoder_step_kernel(B.STEPS[dominant], n_tokens)
     traffic, traffic_src = measured_traffic(w.name, kernel, args.items <= 0)
     res = {
         "metric": "encoder_patches_per_s" if w.cfg.arch != "audio" else "encoder_mel_frames_per_s",
