@@ -109,6 +109,28 @@ constexpr int stages() { return BM == 128 && BN == 160 && NWAVES == 8 ? CS_GEMM_
 template <int BM, int BN, int NWAVES, int EPI>
 constexpr int tile_lds_bytes() { return stages<BM, BN, NWAVES, EPI>() * (BM + BN) * 128 + extra_lds_bytes<BM, BN, NWAVES, EPI>(); }
 constexpr int CHUNK_STRIDE = 144;               // bytes between chunk rows: 128 of data + 16 of padding
+constexpr int CHUNK_BYTES_ = 32 * CHUNK_STRIDE;
+// The 64-row tiles of a ragged last tile row run behind the full tiles, eight of them or so on an otherwise idle
+// chip, each alone on its CU with next to no MFMA work per slice: their K loop goes at the pace of the loads
+// (measured on 8224 x 1024 x 4096: the 32 extra rows cost 29 us on top of 65, 0.45 us per slice).  With eight
+// waves they take as many stage buffers, up to four, as 160 KB of LDS hold (CS_GEMM_LIGHT_STAGES=2 at build time:
+// two): 21 us, 0.33 us per slice, which is 75 GB/s, about what one CU draws; the 8-tile class-token step 9.82 ->
+// 9.51 ms.
+#ifndef CS_GEMM_LIGHT_STAGES
+#define CS_GEMM_LIGHT_STAGES 4
+#endif
+template <int BN, int NWAVES, int EPI>
+constexpr int light_lds_need(int st) {
+  const int stage = (64 + BN) * 128, chunks = NWAVES * CHUNK_BYTES_;
+  return st * stage + extra_lds_bytes<64, BN, NWAVES, EPI>() + (chunks > stage ? chunks : 0);
+}
+template <int BN, int NWAVES, int EPI>
+constexpr int light_stages() {
+  if (NWAVES != 8) return 2;
+  for (int st = CS_GEMM_LIGHT_STAGES; st > 2; --st)
+    if (light_lds_need<BN, NWAVES, EPI>(st) <= 160 * 1024) return st;
+  return 2;
+}
 constexpr int CHUNK_BYTES = 32 * CHUNK_STRIDE;
 
 // v[b][q] holds columns b*32 + blk_col(q) .. +3 of row blk_row(q) of a 32 x (NB*32) block.
@@ -454,7 +476,7 @@ constexpr bool light_tail() {
 
 // One output tile: K loop and epilogue.
 // LDS_ALLOC: bytes of LDS the launch has (that of its largest tile shape).
-template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = tile_lds_bytes<BM, BN, WGM * WGN, EPI>()>
+template <int BM, int BN, int WGM, int WGN, int EPI, int LDS_ALLOC = tile_lds_bytes<BM, BN, WGM * WGN, EPI>(), int STAGES_ARG = 0>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem, const int m0, const int n0) {
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = (WN + 31) / 32;
@@ -468,8 +490,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, unsigned char* smem
   // narrow launch) they go behind everything else this tile uses, inside what the launch's main tile shape allocated
   constexpr bool CHUNKS_BEHIND = NWAVES * CHUNK_BYTES > STAGE_BYTES;
   constexpr int XTRA = extra_lds_bytes<BM, BN, NWAVES, EPI>();
-  constexpr int STAGES = stages<BM, BN, NWAVES, EPI>();
-  static_assert(STAGES == 2 || EPI != EPI_QKV, "the rotary table's place assumes two stage buffers");
+  constexpr int STAGES = STAGES_ARG ? STAGES_ARG : stages<BM, BN, NWAVES, EPI>();
+  // (QKV: behind the K loop the rotary table and the chunks above it take the space of the first two stage buffers)
   static_assert(!CHUNKS_BEHIND || (STAGES * STAGE_BYTES + XTRA + NWAVES * CHUNK_BYTES <= LDS_ALLOC && EPI != EPI_QKV),
                 "no room for the epilogue chunks");
 
@@ -938,6 +960,15 @@ __device__ __forceinline__ void tile_origin(int id, int tiles_m, int tiles_n, in
   n0 = (in_band / band_rows) * BN;
 }
 
+// LDS of a launch: that of its main tile, or what the deeper pipeline of its 64-row tail tiles needs.
+template <int BM, int BN, int NWAVES, int EPI, int TAIL>
+constexpr int launch_lds_bytes() {
+  const int main_tile = tile_lds_bytes<BM, BN, NWAVES, EPI>();
+  if (TAIL != 1 /* TAIL_LIGHT */) return main_tile;
+  const int light = light_lds_need<BN, NWAVES, EPI>(light_stages<BN, NWAVES, EPI>());
+  return light > main_tile ? light : main_tile;
+}
+
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 __global__ __launch_bounds__(64 * WGM * WGN)
 // (the four-wave 128 x 160 tile must leave room for a second workgroup on the CU: 256 registers, not 512)
@@ -981,7 +1012,8 @@ __attribute__((amdgpu_waves_per_eu(BM == 128 && BN == 160 ? 2 : 1))) void gemm_k
     if ((int)blockIdx.x >= n_main) {
       const int t = blockIdx.x - n_main;
       const int tail_m = (M - full_m * BM + 63) / 64;
-      tile_body<64, BN, 1, WGM * WGN, EPI, tile_lds_bytes<BM, BN, WGM * WGN, EPI>()>(g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
+      tile_body<64, BN, 1, WGM * WGN, EPI, launch_lds_bytes<BM, BN, WGM * WGN, EPI, TAIL>(), light_stages<BN, WGM * WGN, EPI>()>(
+          g, smem, full_m * BM + (t % tail_m) * 64, (t / tail_m) * BN);
       return;
     }
     tiles_m = full_m;
@@ -1014,7 +1046,7 @@ static bool tail_split_off() {
 template <int BM, int BN, int WGM, int WGN, int EPI, int TAIL>
 static cs_status launch_one(const GemmArgs& g, hipStream_t stream) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr int LDS = tile_lds_bytes<BM, BN, WGM * WGN, EPI>();
+  constexpr int LDS = launch_lds_bytes<BM, BN, WGM * WGN, EPI, TAIL>();
   static_assert(LDS <= 160 * 1024, "LDS of a CU");
   auto kern = gemm_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   if (g.describe) {
